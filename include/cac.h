@@ -1,0 +1,146 @@
+/*
+ * cac.h -- C ABI of the compressed-activation convolution training step for
+ * AMD MI355X (gfx950).
+ *
+ * The method (paper section "Compressing Activation Maps" and its figure of the
+ * compression scheme): a convolution layer computes its forward output from the
+ * full-resolution input X; what it keeps for the backward pass is not X but
+ * Z = k x k average pooling of X.  In the backward pass the weight gradient is
+ * computed from Z inflated back to the shape of X (every pooled value repeated
+ * over the tile it came from); the data gradient and the bias gradient do not
+ * depend on the activation and stay exact.
+ *
+ * This library never writes the inflated activation to memory: the weight
+ * gradient kernel reads Z and expands it in registers / LDS.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers (HIP global memory) owned by the
+ *     caller, dense, NCHW / KCRS row-major, at least 16-byte aligned.
+ *   - dtype CAC_F32 : X, W, b, Y, Z, dY, dX are float;  dW is float.
+ *     dtype CAC_BF16: X, W, b, Y, Z, dY, dX are bfloat16 (round to nearest even
+ *     on every store), arithmetic accumulates in float; dW is float.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     work is enqueued on it; no entry point synchronises, allocates device
+ *     memory, or keeps state between calls.
+ *   - `ws` is caller-owned device scratch of at least cac_workspace_size()
+ *     bytes (may be NULL when that size is 0).  Its contents are undefined
+ *     after a call.
+ *   - Return value: CAC_OK (0) or a negative cac_status.  Validation happens
+ *     before anything is launched, so a failing call has touched no buffer.
+ *     cac_last_error() gives a thread-local message for the last failing call.
+ *   - No C++ exception crosses this boundary.
+ */
+#ifndef CAC_H
+#define CAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CAC_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum cac_status {
+    CAC_OK = 0,
+    CAC_ERR_INVALID_ARG = -1,      /* NULL pointer, non-positive extent, bad enum, bad desc.size */
+    CAC_ERR_UNSUPPORTED = -2,      /* valid request this build has no kernel for */
+    CAC_ERR_WORKSPACE_TOO_SMALL = -3,
+    CAC_ERR_ALIGNMENT = -4,        /* a tensor pointer is not 16-byte aligned */
+    CAC_ERR_LAUNCH_FAILED = -5     /* HIP reported an error at launch */
+} cac_status;
+
+typedef enum cac_dtype { CAC_F32 = 0, CAC_BF16 = 1 } cac_dtype;
+typedef enum cac_layout { CAC_NCHW = 0, CAC_NHWC = 1 /* not implemented: CAC_ERR_UNSUPPORTED */ } cac_layout;
+
+/* How a pooling tile that sticks out over the edge is treated (the paper is
+ * silent; its memory table implies FLOOR_DROP, every stated invariant needs
+ * CEIL_VALID):
+ *   CEIL_VALID : Hp = ceil(H/kh); a ragged tile is averaged over the elements it
+ *                really has; every pixel of X is covered.            (default)
+ *   FLOOR_DROP : Hp = floor(H/kh); only shape/byte queries accept it when kh
+ *                does not divide H (or kw W); the kernels then return
+ *                CAC_ERR_UNSUPPORTED because the paper does not define what the
+ *                dropped rows inflate to. */
+typedef enum cac_edge_mode { CAC_EDGE_CEIL_VALID = 0, CAC_EDGE_FLOOR_DROP = 1 } cac_edge_mode;
+
+typedef enum cac_op {
+    CAC_OP_FWD_AND_COMPRESS = 0,
+    CAC_OP_BWD_WEIGHT_COMPRESSED = 1,
+    CAC_OP_BWD_DATA = 2,
+    CAC_OP_COMPRESS = 3,
+    CAC_OP_BWD_BIAS = 4
+} cac_op;
+
+/* One convolution layer with a compressed saved input.  Plain data, filled by
+ * the caller.  `size` must be sizeof(cac_desc) (guards against a mismatched
+ * header).  Dilation 1 and groups 1 only. */
+typedef struct cac_desc {
+    uint32_t size;
+    int32_t N;                   /* mini-batch */
+    int32_t C_in, C_out;
+    int32_t H, W;                /* input extent */
+    int32_t R, S;                /* filter extent */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;        /* zero padding on each side */
+    int32_t pool_kh, pool_kw;    /* pooling tile; 1,1 = keep X uncompressed */
+    int32_t edge_mode;           /* cac_edge_mode */
+    int32_t dtype;               /* cac_dtype */
+    int32_t layout;              /* cac_layout */
+    int32_t has_bias;            /* forward adds b[C_out] when non-zero */
+    int32_t deterministic;       /* non-zero: fixed summation order in the split
+                                    weight-gradient reduction (the only mode built) */
+} cac_desc;
+
+int cac_version(void);
+const char *cac_last_error(void);
+
+/* Host only.  Output extent of the convolution: P = floor((H+2*pad_h-R)/stride_h)+1. */
+int cac_out_shape(const cac_desc *d, int32_t *P, int32_t *Q);
+
+/* Host only.  The saved record's book-keeping ("no encoding beyond the original
+ * shape": compression section; byte counts as in the per-layer memory table):
+ * pooled extent and the bytes of X and of Z in the descriptor's dtype. */
+int cac_pooled_shape(const cac_desc *d, int32_t *Hp, int32_t *Wp, size_t *z_bytes, size_t *x_bytes);
+
+/* Host only.  Device scratch bytes the given cac_op needs for this descriptor. */
+int cac_workspace_size(const cac_desc *d, int op, size_t *bytes);
+
+/* Forward pass of the layer plus compression of its input (compression
+ * section: the forward convolution is computed from the uncompressed X, and
+ * only afterwards X is pooled into Z, the tensor that is kept).
+ *   X [N][C_in][H][W], W [C_out][C_in][R][S], b [C_out] or NULL when !has_bias
+ *   Y [N][C_out][P][Q]  = X * W + b           (written)
+ *   Z [N][C_in][Hp][Wp] = block means of X    (written)
+ * After the stream work of this call completes the caller may release X. */
+int conv_fwd_and_compress(const cac_desc *d, const void *X, const void *W, const void *b,
+                          void *Y, void *Z, void *ws, size_t ws_bytes, void *stream);
+
+/* Compression alone (same section): Z = block means of X, for callers whose
+ * producer of X is not this library's forward convolution. */
+int cac_compress(const cac_desc *d, const void *X, void *Z, void *stream);
+
+/* Weight gradient from the compressed activation (weight-gradient formula in
+ * the compression figure): with xhat[n,c,h,w] = Z[n,c,h/kh,w/kw],
+ *   dW[o,c,r,s] = sum_{n,p,q} dY[n,o,p,q] * xhat[n,c,p*stride_h+r-pad_h,q*stride_w+s-pad_w]
+ * (terms outside the image are zero).  dW [C_out][C_in][R][S] float is
+ * OVERWRITTEN, not accumulated into.  xhat is never stored. */
+int conv_bwd_weight_compressed(const cac_desc *d, const void *Z, const void *dY, void *dW,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/* Data gradient (data-gradient formula in the same figure), independent of the
+ * activation and therefore exact:
+ *   dX[n,c,h,w] = sum_{o,r,s} W[o,c,r,s] * dY[n,o,p,q],  p*stride_h+r-pad_h = h, q*stride_w+s-pad_w = w
+ * dX [N][C_in][H][W] is overwritten. */
+int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/* Bias gradient (bias-gradient formula in the same figure): db[o] = sum_{n,p,q} dY.
+ * db [C_out] float is overwritten. */
+int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAC_H */

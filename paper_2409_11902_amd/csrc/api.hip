@@ -1,0 +1,211 @@
+// C ABI of the library: descriptor validation, shape/workspace queries (host
+// only) and dispatch to the kernels.  Every check runs before anything is
+// launched, so all error paths can be exercised without a GPU.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace cac {
+
+static thread_local char g_err[256] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static const long kMaxElems = (1L << 31) - 1; // every tensor is indexed with int-sized extents
+
+// Validates the descriptor and fills the kernel geometry.  `for_kernel`: also
+// reject what only the shape queries accept.
+static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
+{
+    if (!d) return fail(CAC_ERR_INVALID_ARG, "descriptor is NULL");
+    if (d->size != sizeof(cac_desc))
+        return fail(CAC_ERR_INVALID_ARG, "desc.size is %u, this library expects %zu", d->size, sizeof(cac_desc));
+    if (d->N <= 0 || d->C_in <= 0 || d->C_out <= 0 || d->H <= 0 || d->W <= 0)
+        return fail(CAC_ERR_INVALID_ARG, "N, C_in, C_out, H, W must be positive");
+    if (d->R <= 0 || d->S <= 0 || d->stride_h <= 0 || d->stride_w <= 0)
+        return fail(CAC_ERR_INVALID_ARG, "R, S and strides must be positive");
+    if (d->pad_h < 0 || d->pad_w < 0) return fail(CAC_ERR_INVALID_ARG, "padding must be non-negative");
+    if (d->pool_kh <= 0 || d->pool_kw <= 0) return fail(CAC_ERR_INVALID_ARG, "pooling tile must be positive");
+    if (d->dtype != CAC_F32 && d->dtype != CAC_BF16) return fail(CAC_ERR_INVALID_ARG, "unknown dtype %d", d->dtype);
+    if (d->layout != CAC_NCHW && d->layout != CAC_NHWC)
+        return fail(CAC_ERR_INVALID_ARG, "unknown layout %d", d->layout);
+    if (d->edge_mode != CAC_EDGE_CEIL_VALID && d->edge_mode != CAC_EDGE_FLOOR_DROP)
+        return fail(CAC_ERR_INVALID_ARG, "unknown edge_mode %d", d->edge_mode);
+    if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S)
+        return fail(CAC_ERR_INVALID_ARG, "filter larger than the padded input");
+    bool floor_mode = d->edge_mode == CAC_EDGE_FLOOR_DROP;
+    if (floor_mode && (d->H < d->pool_kh || d->W < d->pool_kw))
+        return fail(CAC_ERR_INVALID_ARG, "floor/drop pooling tile larger than the input");
+
+    g->N = d->N; g->C = d->C_in; g->K = d->C_out; g->H = d->H; g->W = d->W;
+    g->R = d->R; g->S = d->S; g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+    g->Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    g->kh = d->pool_kh; g->kw = d->pool_kw;
+    g->Hp = floor_mode ? d->H / d->pool_kh : (d->H + d->pool_kh - 1) / d->pool_kh;
+    g->Wp = floor_mode ? d->W / d->pool_kw : (d->W + d->pool_kw - 1) / d->pool_kw;
+
+    if (!for_kernel) return CAC_OK;
+    if (d->layout != CAC_NCHW) return fail(CAC_ERR_UNSUPPORTED, "only the NCHW layout is implemented");
+    if (floor_mode && (d->H % d->pool_kh || d->W % d->pool_kw))
+        return fail(CAC_ERR_UNSUPPORTED,
+                    "floor/drop edge mode with a tile that does not divide the input: inflation of the dropped "
+                    "rows is undefined; use CAC_EDGE_CEIL_VALID");
+    if (!d->deterministic)
+        return fail(CAC_ERR_UNSUPPORTED, "only the deterministic weight-gradient reduction is implemented");
+    long x = (long)g->N * g->C * g->H * g->W, y = (long)g->N * g->K * g->P * g->Q;
+    long w = (long)g->K * g->C * g->R * g->S;
+    if (x > kMaxElems || y > kMaxElems || w > kMaxElems)
+        return fail(CAC_ERR_UNSUPPORTED, "a tensor has more than 2^31-1 elements");
+    if (g->N > 65535) return fail(CAC_ERR_UNSUPPORTED, "N above 65535");
+    return CAC_OK;
+}
+
+static int check_ptr(const void *p, const char *name)
+{
+    if (!p) return fail(CAC_ERR_INVALID_ARG, "%s is NULL", name);
+    if (((uintptr_t)p) & 15) return fail(CAC_ERR_ALIGNMENT, "%s is not 16-byte aligned", name);
+    return CAC_OK;
+}
+
+static int check_ws(const Geom &g, int dtype, int op, const void *ws, size_t ws_bytes, size_t *need_out);
+
+static int launched(hipError_t e, const char *what)
+{
+    if (e != hipSuccess) return fail(CAC_ERR_LAUNCH_FAILED, "%s: %s", what, hipGetErrorString(e));
+    return CAC_OK;
+}
+
+static size_t workspace_bytes(const Geom &g, int dtype, int op)
+{
+    (void)g; (void)dtype; (void)op;
+    return 0;
+}
+
+static int check_ws(const Geom &g, int dtype, int op, const void *ws, size_t ws_bytes, size_t *need_out)
+{
+    size_t need = workspace_bytes(g, dtype, op);
+    if (need_out) *need_out = need;
+    if (need == 0) return CAC_OK;
+    if (!ws) return fail(CAC_ERR_WORKSPACE_TOO_SMALL, "workspace is NULL, %zu bytes needed", need);
+    if (((uintptr_t)ws) & 15) return fail(CAC_ERR_ALIGNMENT, "workspace is not 16-byte aligned");
+    if (ws_bytes < need) return fail(CAC_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+    return CAC_OK;
+}
+
+static hipError_t do_compress(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st)
+{
+    return launch_compress_generic(g, dtype, X, Z, st);
+}
+
+} // namespace cac
+
+using namespace cac;
+
+extern "C" {
+
+int cac_version(void) { return CAC_VERSION; }
+
+const char *cac_last_error(void) { return g_err; }
+
+int cac_out_shape(const cac_desc *d, int32_t *P, int32_t *Q)
+{
+    Geom g;
+    int rc = make_geom(d, &g, false);
+    if (rc) return rc;
+    if (!P || !Q) return fail(CAC_ERR_INVALID_ARG, "output pointer is NULL");
+    *P = g.P;
+    *Q = g.Q;
+    return CAC_OK;
+}
+
+int cac_pooled_shape(const cac_desc *d, int32_t *Hp, int32_t *Wp, size_t *z_bytes, size_t *x_bytes)
+{
+    Geom g;
+    int rc = make_geom(d, &g, false);
+    if (rc) return rc;
+    size_t eb = d->dtype == CAC_F32 ? 4 : 2;
+    if (Hp) *Hp = g.Hp;
+    if (Wp) *Wp = g.Wp;
+    if (z_bytes) *z_bytes = (size_t)g.N * g.C * g.Hp * g.Wp * eb;
+    if (x_bytes) *x_bytes = (size_t)g.N * g.C * g.H * g.W * eb;
+    return CAC_OK;
+}
+
+int cac_workspace_size(const cac_desc *d, int op, size_t *bytes)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_BIAS) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    if (!bytes) return fail(CAC_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = workspace_bytes(g, d->dtype, op);
+    return CAC_OK;
+}
+
+int conv_fwd_and_compress(const cac_desc *d, const void *X, const void *W, const void *b, void *Y, void *Z,
+                          void *ws, size_t ws_bytes, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(X, "X")) || (rc = check_ptr(W, "W")) || (rc = check_ptr(Y, "Y")) || (rc = check_ptr(Z, "Z")))
+        return rc;
+    if (d->has_bias && (rc = check_ptr(b, "b"))) return rc;
+    if ((rc = check_ws(g, d->dtype, CAC_OP_FWD_AND_COMPRESS, ws, ws_bytes, nullptr))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = launched(launch_fwd_generic(g, d->dtype, X, W, d->has_bias ? b : nullptr, Y, st), "forward convolution")))
+        return rc;
+    return launched(do_compress(g, d->dtype, X, Z, st), "compress");
+}
+
+int cac_compress(const cac_desc *d, const void *X, void *Z, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(X, "X")) || (rc = check_ptr(Z, "Z"))) return rc;
+    return launched(do_compress(g, d->dtype, X, Z, (hipStream_t)stream), "compress");
+}
+
+int conv_bwd_weight_compressed(const cac_desc *d, const void *Z, const void *dY, void *dW, void *ws,
+                               size_t ws_bytes, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(Z, "Z")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dW, "dW"))) return rc;
+    if ((rc = check_ws(g, d->dtype, CAC_OP_BWD_WEIGHT_COMPRESSED, ws, ws_bytes, nullptr))) return rc;
+    return launched(launch_dw_generic(g, d->dtype, Z, dY, (float *)dW, (hipStream_t)stream), "weight gradient");
+}
+
+int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX, void *ws, size_t ws_bytes,
+                  void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(W, "W")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dX, "dX"))) return rc;
+    if ((rc = check_ws(g, d->dtype, CAC_OP_BWD_DATA, ws, ws_bytes, nullptr))) return rc;
+    return launched(launch_dx_generic(g, d->dtype, W, dY, dX, (hipStream_t)stream), "data gradient");
+}
+
+int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(dY, "dY")) || (rc = check_ptr(db, "db"))) return rc;
+    return launched(launch_db(g, d->dtype, dY, (float *)db, (hipStream_t)stream), "bias gradient");
+}
+
+} // extern "C"

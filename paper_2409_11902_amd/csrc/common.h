@@ -1,0 +1,53 @@
+// Shared device/host definitions of the HIP path (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cac.h"
+
+namespace cac {
+
+// Geometry handed to every kernel by value.
+struct Geom {
+    int N, C, K;        // batch, input channels, output channels
+    int H, W;           // input extent
+    int R, S;           // filter extent
+    int sh, sw, ph, pw; // stride, zero padding
+    int P, Q;           // output extent
+    int kh, kw;         // pooling tile
+    int Hp, Wp;         // pooled extent (ceil)
+};
+
+typedef uint16_t bf16_t; // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// Round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float *p) { return *p; }
+    static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static __device__ __forceinline__ float load(const bf16_t *p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---- launchers implemented in the .hip files.  All enqueue on `st` and return the
+// launch status; operand shapes have been validated by the caller (api.hip).
+hipError_t launch_compress_generic(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st);
+hipError_t launch_fwd_generic(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y,
+                              hipStream_t st);
+hipError_t launch_dx_generic(const Geom &g, int dtype, const void *W, const void *dY, void *dX, hipStream_t st);
+hipError_t launch_dw_generic(const Geom &g, int dtype, const void *Z, const void *dY, float *dW, hipStream_t st);
+hipError_t launch_db(const Geom &g, int dtype, const void *dY, float *db, hipStream_t st);
+
+} // namespace cac

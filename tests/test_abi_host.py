@@ -1,0 +1,144 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, answers the shape/byte queries bit-exactly, and rejects bad
+requests before anything could be launched.  No compute call needs a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2409_11902_amd import binding as B
+from paper_2409_11902_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+MiB = float(1 << 20)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "cac.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b((?:cac|conv)_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert B.cac_version() == 100
+
+
+def test_desc_layout_matches_header():
+    hdr = open(os.path.join(ROOT, "include", "cac.h")).read()
+    body = re.search(r"typedef struct cac_desc \{(.*?)\} cac_desc;", hdr, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if decl:
+            names += [n.strip() for n in decl.split(None, 1)[1].split(",")]
+    assert names == [f[0] for f in B.cac_desc._fields_]
+    assert ctypes.sizeof(B.cac_desc) == 4 * len(names)
+
+
+@pytest.mark.parametrize("hw", [(56, 56), (28, 28), (14, 14), (7, 7), (5, 9), (224, 224)])
+@pytest.mark.parametrize("k", [(1, 1), (2, 2), (4, 4), (2, 4)])
+@pytest.mark.parametrize("mode", [B.EDGE_CEIL_VALID, B.EDGE_FLOOR_DROP])
+def test_pooled_shape_bit_exact_vs_oracle(hw, k, mode):
+    H, W = hw
+    for dtype, eb in ((B.F32, 4), (B.BF16, 2)):
+        d = B.make_desc(32, 64, 64, H, W, 3, 3, 1, 1, 1, 1, k[0], k[1], edge_mode=mode, dtype=dtype)
+        hp, wp, zb, xb = B.cac_pooled_shape(d)
+        assert (hp, wp) == oracle.pooled_shape(H, W, k[0], k[1], mode)
+        assert (xb, zb) == oracle.saved_bytes(32, 64, H, W, k[0], k[1], eb, mode)
+
+
+def test_table1_bytes_from_the_library(golden_dir):
+    """Per-layer memory table, reproduced by the library's own book-keeping
+    (floor/drop shapes, 4-byte elements, mini-batch 32)."""
+    sums = [0.0, 0.0, 0.0]
+    for line in open(os.path.join(golden_dir, "table1_memory.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "Sum":
+            for mine, printed in zip(sums, map(float, f[4:7])):
+                assert abs(mine - printed) <= 0.0051
+            continue
+        C, H, W = int(f[1]), int(f[2]), int(f[3])
+        vals = []
+        for k in (1, 2, 4):
+            d = B.make_desc(32, C, 64, H, W, 3, 3, 1, 1, 1, 1, k, k, edge_mode=B.EDGE_FLOOR_DROP, dtype=B.F32)
+            _, _, zb, xb = B.cac_pooled_shape(d)
+            vals.append(zb / MiB)
+            assert k != 1 or zb == xb
+        for i, (mine, printed) in enumerate(zip(vals, map(float, f[4:7]))):
+            assert abs(mine - printed) <= 0.0051, (f[0], vals)
+            sums[i] += mine
+
+
+def test_out_shape():
+    for spec in sum(synth.configs().values(), []):
+        d = B.desc_from_spec(spec)
+        assert B.cac_out_shape(d) == (spec.P, spec.Q)
+
+
+def _expect(code, fn, *a):
+    with pytest.raises(B.CacError) as e:
+        fn(*a)
+    assert e.value.code == code, str(e.value)
+    assert len(str(e.value)) > 20
+
+
+def test_invalid_descriptors_are_rejected():
+    good = dict(N=2, C_in=4, C_out=4, H=8, W=8, R=3, S=3, pad_h=1, pad_w=1)
+    for bad in (dict(N=0), dict(C_in=-1), dict(H=0), dict(R=0), dict(stride_h=0), dict(pad_w=-1),
+                dict(pool_kh=0), dict(dtype=7), dict(layout=5), dict(edge_mode=3), dict(R=11, pad_h=0)):
+        d = B.make_desc(**{**good, **bad})
+        _expect(B.ERR_INVALID_ARG, B.cac_pooled_shape, d)
+    d = B.make_desc(**good)
+    d.size = 12
+    _expect(B.ERR_INVALID_ARG, B.cac_pooled_shape, d)
+    rc = B.lib().cac_pooled_shape(None, None, None, None, None)
+    assert rc == B.ERR_INVALID_ARG
+
+
+def test_unsupported_requests():
+    good = dict(N=2, C_in=4, C_out=4, H=7, W=7, R=3, S=3, pad_h=1, pad_w=1)
+    _expect(B.ERR_UNSUPPORTED, B.cac_workspace_size, B.make_desc(**good, layout=B.NHWC), B.OP_BWD_DATA)
+    _expect(B.ERR_UNSUPPORTED, B.cac_workspace_size, B.make_desc(**good, edge_mode=B.EDGE_FLOOR_DROP), B.OP_COMPRESS)
+    _expect(B.ERR_UNSUPPORTED, B.cac_workspace_size, B.make_desc(**good, deterministic=0), B.OP_BWD_WEIGHT_COMPRESSED)
+    # floor/drop is fine when the tile divides the input
+    ok = B.make_desc(**{**good, "H": 8, "W": 8}, edge_mode=B.EDGE_FLOOR_DROP)
+    assert B.cac_workspace_size(ok, B.OP_COMPRESS) >= 0
+    _expect(B.ERR_INVALID_ARG, B.cac_workspace_size, B.make_desc(**good), 99)
+
+
+def test_null_and_misaligned_pointers_fail_before_any_launch():
+    """These calls would touch the GPU if validation let them through; on a
+    machine without one they still return the validation error."""
+    L = B.lib()
+    d = B.make_desc(2, 4, 4, 8, 8, 3, 3, 1, 1, 1, 1)
+    p = ctypes.byref(d)
+    a = ctypes.c_void_p(0x1000)      # aligned, never dereferenced by the host
+    m = ctypes.c_void_p(0x1004)      # misaligned
+    assert L.conv_fwd_and_compress(p, None, a, a, a, a, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.conv_fwd_and_compress(p, a, a, None, a, a, None, 0, None) == B.ERR_INVALID_ARG  # has_bias, b NULL
+    assert L.conv_fwd_and_compress(p, a, m, a, a, a, None, 0, None) == B.ERR_ALIGNMENT
+    assert L.cac_compress(p, a, None, None) == B.ERR_INVALID_ARG
+    assert L.cac_compress(p, m, a, None) == B.ERR_ALIGNMENT
+    assert L.conv_bwd_weight_compressed(p, a, None, a, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.conv_bwd_weight_compressed(p, a, a, m, None, 0, None) == B.ERR_ALIGNMENT
+    assert L.conv_bwd_data(p, None, a, a, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.conv_bwd_bias(p, a, None, None) == B.ERR_INVALID_ARG
+    assert b"NULL" in L.cac_last_error()
+
+
+def test_workspace_too_small_is_reported():
+    L = B.lib()
+    for spec in (synth.configs()["cfg2_resnet18_cifar"][0], synth.configs()["cfg5_deep_small_spatial"][1]):
+        d = B.desc_from_spec(spec)
+        need = B.cac_workspace_size(d, B.OP_BWD_WEIGHT_COMPRESSED)
+        if need == 0:
+            continue
+        a = ctypes.c_void_p(0x1000)
+        assert L.conv_bwd_weight_compressed(ctypes.byref(d), a, a, a, a, need - 1, None) == B.ERR_WORKSPACE_TOO_SMALL
+        assert L.conv_bwd_weight_compressed(ctypes.byref(d), a, a, a, None, 0, None) == B.ERR_WORKSPACE_TOO_SMALL

@@ -1,0 +1,169 @@
+"""Parity of the HIP path against the CPU oracle, element by element, on the
+same seeded inputs.  Every call goes through the C ABI (ctypes binding).
+
+Tolerances (relative L2 error ||got - want|| / ||want||):
+  float path    <= 1e-5   (true fp32 multiply-accumulate)
+  bfloat16 path <= 2e-2   (bf16 storage incl. the stored Z, fp32 accumulation)
+and, in addition, a tight check that isolates indexing from storage rounding:
+the oracle is also run from its own Z rounded to bfloat16 by the harness, which
+the device result must match to 2e-4 (only the summation order differs).
+Shapes, byte counts: bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2409_11902_amd import synth
+from util import geom, rel_l2, tile_constant_activation
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.F32: 1e-5, synth.BF16: 2e-2}
+TIGHT = 2e-4
+
+
+def _oracle_step(spec, t, has_bias=True):
+    g = geom(spec)
+    X, Wt, b, dY = (t[k].astype(np.float64) for k in ("X", "W", "b", "dY"))
+    Z = oracle.avgpool(X, spec.k, spec.k)
+    Xh = oracle.inflate(Z, spec.H, spec.W, spec.k, spec.k)
+    return dict(Y=oracle.conv_fwd(g, X, Wt, b if has_bias else None), Z=Z, dW=oracle.conv_dw(g, Xh, dY),
+                dX=oracle.conv_dx(g, Wt, dY), db=oracle.bias_grad(dY))
+
+
+def _check_step(spec, t, got, has_bias=True):
+    want = _oracle_step(spec, t, has_bias)
+    tol = TOL[spec.dtype]
+    for name in ("Y", "Z", "dW", "dX", "db"):
+        assert got[name].shape == want[name].shape, name
+        err = rel_l2(got[name], want[name])
+        assert err <= tol, f"{spec.name} {name}: rel-L2 {err:.3e} > {tol}"
+    g = geom(spec)
+    if spec.dtype == synth.BF16:
+        # tight: same storage rounding of Z on both sides
+        Zr = synth.round_to_bf16(want["Z"].astype(np.float32)).astype(np.float64)
+        ulp_off = np.abs(got["Z"] - Zr) > np.abs(Zr) * 2.0 ** -7
+        assert ulp_off.mean() == 0.0, f"{spec.name}: Z differs by more than one bf16 ulp"
+        dWr = oracle.conv_dw(g, oracle.inflate(Zr, spec.H, spec.W, spec.k, spec.k), t["dY"].astype(np.float64))
+        err = rel_l2(got["dW"], dWr)
+        assert err <= TIGHT, f"{spec.name} dW (tight): rel-L2 {err:.3e}"
+    else:
+        err = rel_l2(got["dW"], want["dW"])
+        assert err <= 1e-5
+
+
+def test_config1_single_conv_fp32():
+    from gpu_util import run_step
+    spec = synth.configs()["cfg1_single_fp32"][0]
+    t = synth.make_inputs(spec, "cfg1_single_fp32")
+    got = run_step(spec, t)
+    _check_step(spec, t, got)
+
+
+# small shapes that still span several tiles and ragged tails; asymmetric on purpose
+SMALL = [
+    # name, N, C, K, H, W, R, S, stride, pad, k
+    ("3x3 ragged 7", 3, 5, 6, 7, 7, 3, 3, 1, 1, 2),
+    ("3x3 14 k4", 2, 8, 4, 14, 14, 3, 3, 1, 1, 4),
+    ("3x3 s2 odd", 2, 6, 10, 15, 15, 3, 3, 2, 1, 2),
+    ("1x1", 4, 16, 8, 8, 8, 1, 1, 1, 0, 2),
+    ("1x1 s2", 4, 8, 16, 14, 14, 1, 1, 2, 0, 2),
+    ("3x3 k1", 2, 4, 4, 9, 9, 3, 3, 1, 1, 1),
+    ("5x5 pad2", 2, 3, 5, 12, 12, 5, 5, 1, 2, 2),
+    ("3x3 nopad", 2, 4, 4, 10, 10, 3, 3, 1, 0, 2),
+    ("7x7 s2 pad3", 1, 3, 8, 20, 20, 7, 7, 2, 3, 2),
+    ("tiny 1px", 1, 1, 1, 1, 1, 1, 1, 1, 0, 2),
+    ("k larger than map", 2, 3, 3, 3, 3, 3, 3, 1, 1, 4),
+    ("wide channels", 2, 70, 33, 6, 6, 3, 3, 1, 1, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_small_shapes(case, dtype):
+    from gpu_util import run_step
+    name, N, C, K, H, W, R, S, st, pad, k = case
+    spec = synth.LayerSpec(name, N, C, K, H, W, R, S, st, pad, k, dtype)
+    t = synth.make_inputs(spec, "small")
+    got = run_step(spec, t)
+    _check_step(spec, t, got)
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_rectangular_and_anisotropic(dtype):
+    """H != W, R != S, stride/pad/pooling tile different per axis (descriptor fields
+    the LayerSpec shorthand does not cover)."""
+    from gpu_util import run_step
+    spec = synth.LayerSpec("rect", 2, 6, 5, 10, 17, 3, 3, 1, 1, 2, dtype)
+    over = dict(R=3, S=2, stride_h=2, stride_w=1, pad_h=1, pad_w=0, pool_kh=2, pool_kw=4)
+    g = oracle.ConvGeom(2, 6, 5, 10, 17, 3, 2, 2, 1, 1, 0)
+    rng = np.random.Generator(np.random.Philox(key=77))
+    t = dict(X=synth.to_storage(np.maximum(rng.standard_normal((2, 6, 10, 17), dtype=np.float32), 0), dtype),
+             W=synth.to_storage(rng.standard_normal((5, 6, 3, 2), dtype=np.float32), dtype),
+             b=synth.to_storage(rng.standard_normal((5,), dtype=np.float32), dtype),
+             dY=synth.to_storage(rng.standard_normal((2, 5, g.P, g.Q), dtype=np.float32), dtype))
+    # run_step sizes its buffers from the spec: give it one whose P, Q, R, S match
+    from paper_2409_11902_amd import binding as B
+    import torch
+    from gpu_util import Guarded, upload, download, tdtype, workspace
+    d = B.desc_from_spec(spec, **over)
+    hp, wp, zb, xb = B.cac_pooled_shape(d)
+    assert (hp, wp) == oracle.pooled_shape(10, 17, 2, 4) and B.cac_out_shape(d) == (g.P, g.Q)
+    td = tdtype(spec)
+    X, Wt, b, dY = (upload(t[k], dtype) for k in ("X", "W", "b", "dY"))
+    Y, Z = Guarded((2, 5, g.P, g.Q), td), Guarded((2, 6, hp, wp), td)
+    dW, dX, db = Guarded((5, 6, 3, 2), torch.float32), Guarded((2, 6, 10, 17), td), Guarded((5,), torch.float32)
+    B.conv_fwd_and_compress(d, X, Wt, b, Y.t, Z.t, workspace(d, B.OP_FWD_AND_COMPRESS))
+    B.conv_bwd_weight_compressed(d, Z.t, dY, dW.t, workspace(d, B.OP_BWD_WEIGHT_COMPRESSED))
+    B.conv_bwd_data(d, Wt, dY, dX.t, workspace(d, B.OP_BWD_DATA))
+    B.conv_bwd_bias(d, dY, db.t)
+    torch.cuda.synchronize()
+    for gb in (Y, Z, dW, dX, db):
+        gb.check("rect")
+    f = {k: v.astype(np.float64) for k, v in t.items()}
+    Zo = oracle.avgpool(f["X"], 2, 4)
+    want = dict(Y=oracle.conv_fwd(g, f["X"], f["W"], f["b"]), Z=Zo,
+                dW=oracle.conv_dw(g, oracle.inflate(Zo, 10, 17, 2, 4), f["dY"]),
+                dX=oracle.conv_dx(g, f["W"], f["dY"]), db=oracle.bias_grad(f["dY"]))
+    got = dict(Y=Y, Z=Z, dW=dW, dX=dX, db=db)
+    for name in want:
+        err = rel_l2(download(got[name].t), want[name])
+        assert err <= TOL[dtype], f"{name}: {err:.3e}"
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_invariants_on_device(dtype):
+    """k = 1 stores X itself; Y and dX do not depend on k (they never see Z);
+    a tile-constant activation is compressed without loss."""
+    from gpu_util import run_step
+    base = synth.LayerSpec("inv", 3, 8, 8, 12, 12, 3, 3, 1, 1, 1, dtype)
+    t = synth.make_inputs(base, "inv")
+    res = {k: run_step(base.with_k(k), t) for k in (1, 2, 4)}
+    assert np.array_equal(res[1]["Z"], t["X"].astype(np.float64))           # bit-exact copy
+    g = geom(base)
+    exact = oracle.conv_dw(g, t["X"].astype(np.float64), t["dY"].astype(np.float64))
+    assert rel_l2(res[1]["dW"], exact) <= (1e-5 if dtype == synth.F32 else TIGHT)
+    for k in (2, 4):
+        assert np.array_equal(res[k]["Y"], res[1]["Y"])
+        assert np.array_equal(res[k]["dX"], res[1]["dX"])
+        assert np.array_equal(res[k]["db"], res[1]["db"])
+        assert not np.array_equal(res[k]["dW"], res[1]["dW"])
+    for k in (2, 4):
+        spec = base.with_k(k)
+        tc = dict(t, X=tile_constant_activation(spec))
+        lossy = run_step(spec, tc)
+        ref = run_step(spec.with_k(1), tc)
+        assert rel_l2(lossy["dW"], ref["dW"]) <= 1e-5
+        # average pooling keeps every channel's sum (up to storage rounding of Z)
+    spec = base.with_k(2)
+    Zsum = res[2]["Z"].sum(axis=(2, 3)) * 4
+    np.testing.assert_allclose(Zsum, t["X"].astype(np.float64).sum(axis=(2, 3)),
+                               rtol=1e-5 if dtype == synth.F32 else 4e-3)
+
+
+def test_no_bias_and_empty_free_paths():
+    from gpu_util import run_step
+    spec = synth.LayerSpec("nobias", 2, 4, 6, 8, 8, 3, 3, 1, 1, 2, synth.F32)
+    t = synth.make_inputs(spec, "nobias")
+    got = run_step(spec, t, has_bias=False)
+    _check_step(spec, t, got, has_bias=False)
