@@ -107,6 +107,11 @@ int cac_pooled_shape(const cac_desc *d, int32_t *Hp, int32_t *Wp, size_t *z_byte
 /* Host only.  Device scratch bytes the given cac_op needs for this descriptor. */
 int cac_workspace_size(const cac_desc *d, int op, size_t *bytes);
 
+/* Host only.  Writes a one-line, human-readable description of the kernel and
+ * launch shape the given cac_op would use for this descriptor into buf (always
+ * NUL-terminated, truncated to buf_len).  For logs and benchmarks. */
+int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len);
+
 /* Forward pass of the layer plus compression of its input (compression
  * section: the forward convolution is computed from the uncompressed X, and
  * only afterwards X is pooled into Z, the tensor that is kept).

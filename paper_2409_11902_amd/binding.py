@@ -24,7 +24,7 @@ EDGE_CEIL_VALID, EDGE_FLOOR_DROP = 0, 1
 OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS = range(5)
 
 EXPORTS = (
-    "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size",
+    "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size", "cac_describe_plan",
     "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias",
 )
 
@@ -64,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.cac_out_shape.argtypes = [dp, ip, ip]
         L.cac_pooled_shape.argtypes = [dp, ip, ip, szp, szp]
         L.cac_workspace_size.argtypes = [dp, ctypes.c_int, szp]
+        L.cac_describe_plan.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, sz]
         L.conv_fwd_and_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cac_compress.argtypes = [dp, vp, vp, vp]
         L.conv_bwd_weight_compressed.argtypes = [dp, vp, vp, vp, vp, sz, vp]
@@ -118,6 +119,12 @@ def cac_workspace_size(d: cac_desc, op: int) -> int:
     b = ctypes.c_size_t()
     _check(lib().cac_workspace_size(ctypes.byref(d), op, ctypes.byref(b)))
     return b.value
+
+
+def cac_describe_plan(d: cac_desc, op: int) -> str:
+    buf = ctypes.create_string_buffer(512)
+    _check(lib().cac_describe_plan(ctypes.byref(d), op, buf, len(buf)))
+    return buf.value.decode()
 
 
 def _ptr(t):

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include "common.h"
+#include "dw_mfma.h"
 
 namespace cac {
 
@@ -87,7 +88,10 @@ static int launched(hipError_t e, const char *what)
 
 static size_t workspace_bytes(const Geom &g, int dtype, int op)
 {
-    (void)g; (void)dtype; (void)op;
+    if (op == CAC_OP_BWD_WEIGHT_COMPRESSED) {
+        DwMfmaPlan plan;
+        if (dw_mfma_plan(g, dtype, &plan)) return plan.partial_bytes; // partial sums of the pixel slices
+    }
     return 0;
 }
 
@@ -152,6 +156,28 @@ int cac_workspace_size(const cac_desc *d, int op, size_t *bytes)
     return CAC_OK;
 }
 
+int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if (!buf || buf_len == 0) return fail(CAC_ERR_INVALID_ARG, "buf is NULL or empty");
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_BIAS) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    DwMfmaPlan plan;
+    if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && dw_mfma_plan(g, d->dtype, &plan)) {
+        const DwMfmaParams &p = plan.p;
+        snprintf(buf, buf_len,
+                 "dw_mfma variant=%d tile=64x64 chunk=%dimg x %drows (LR=%d/%d SEGS=%d NZ=%d XW=%d) items dy=%d z=%d "
+                 "passes dy=%d z=%d vec dy=%d z=%d lds=%dB chunks=%d slices=%d x %d tiles grid=%u partial=%zuB",
+                 plan.variant, p.NBI, p.PR, p.LR, p.LRpad, p.SEGS, p.NZ, p.XW, p.rowitems, p.citems, p.dy_passes,
+                 p.z_passes, p.dy_vec, p.z_vec, p.lds_bytes, p.nchunks, p.nslices, p.tiles_o * p.tiles_c, plan.grid,
+                 plan.partial_bytes);
+    } else {
+        snprintf(buf, buf_len, "generic kernel");
+    }
+    return CAC_OK;
+}
+
 int conv_fwd_and_compress(const cac_desc *d, const void *X, const void *W, const void *b, void *Y, void *Z,
                           void *ws, size_t ws_bytes, void *stream)
 {
@@ -185,6 +211,9 @@ int conv_bwd_weight_compressed(const cac_desc *d, const void *Z, const void *dY,
     if (rc) return rc;
     if ((rc = check_ptr(Z, "Z")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dW, "dW"))) return rc;
     if ((rc = check_ws(g, d->dtype, CAC_OP_BWD_WEIGHT_COMPRESSED, ws, ws_bytes, nullptr))) return rc;
+    DwMfmaPlan plan;
+    if (dw_mfma_plan(g, d->dtype, &plan))
+        return launched(launch_dw_mfma(plan, Z, dY, (float *)dW, ws, (hipStream_t)stream), "weight gradient (MFMA)");
     return launched(launch_dw_generic(g, d->dtype, Z, dY, (float *)dW, (hipStream_t)stream), "weight gradient");
 }
 
