@@ -1,0 +1,297 @@
+#!/usr/bin/env python3
+"""Benchmark of the compressed-activation convolution training step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of seeded synthetic
+input: for every layer of the workload, conv_fwd_and_compress (forward conv +
+pooling of the saved input), conv_bwd_weight_compressed (dW from the pooled map)
+and conv_bwd_data.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line on stdout; tables go to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2_resnet18_cifar")
+    ap.add_argument("--layers", default="", help="comma-separated layer indices of the workload (default all)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", choices=["", "dw", "compress", "fwd", "dx"],
+                    help="profiling aid: run just this entry point --steps times per layer and exit")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+class Layer:
+    """Device buffers of one layer of the workload."""
+
+    def __init__(self, spec, config, B, synth, torch):
+        upload = B.to_device
+        self.spec = spec
+        self.d = B.desc_from_spec(spec)
+        hp, wp, self.z_bytes, self.x_bytes = B.cac_pooled_shape(self.d)
+        t = synth.make_inputs(spec, config)
+        self.host = t
+        td = torch.float32 if spec.dtype == synth.F32 else torch.bfloat16
+        dev = "cuda:0"
+        self.X, self.W, self.b, self.dY = (upload(t[k], spec.dtype) for k in ("X", "W", "b", "dY"))
+        self.Y = torch.empty((spec.N, spec.K, spec.P, spec.Q), dtype=td, device=dev)
+        self.Z = torch.empty((spec.N, spec.C, hp, wp), dtype=td, device=dev)
+        self.dW = torch.empty((spec.K, spec.C, spec.R, spec.S), dtype=torch.float32, device=dev)
+        self.dX = torch.empty((spec.N, spec.C, spec.H, spec.W), dtype=td, device=dev)
+        self.ws = {}
+        for op in (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA):
+            n = B.cac_workspace_size(self.d, op)
+            self.ws[op] = torch.empty(max(n, 16), dtype=torch.uint8, device=dev) if n else None
+        self.plan = B.cac_describe_plan(self.d, B.OP_BWD_WEIGHT_COMPRESSED)
+        eb = spec.elem_bytes
+        self.flops = {
+            "fwd": 2 * spec.N * spec.P * spec.Q * spec.K * spec.C * spec.R * spec.S,
+            "dw": spec.dw_flops,
+            "dx": 2 * spec.N * spec.P * spec.Q * spec.K * spec.C * spec.R * spec.S,
+        }
+        # algorithmic bytes: compress reads X and writes Z; dW reads Z and dY, writes dW
+        self.bytes = {
+            "compress": self.x_bytes + self.z_bytes,
+            "dw": self.z_bytes + spec.N * spec.K * spec.P * spec.Q * eb + spec.K * spec.C * spec.R * spec.S * 4,
+        }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1. "
+                 "The path would shard over the batch with one all-reduce of dW; see DESIGN.md.")
+    import numpy as np
+    import torch
+
+    from paper_2409_11902_amd import binding as B
+    from paper_2409_11902_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()  # fail loudly if the native library is missing
+    cfgs = synth.configs()
+    specs = cfgs[args.workload]
+    if args.layers:
+        specs = [specs[int(i)] for i in args.layers.split(",")]
+    t0 = time.time()
+    layers = [Layer(s, args.workload, B, synth, torch) for s in specs]
+    torch.cuda.synchronize()
+    log(f"[bench] {args.workload}: {len(layers)} layers set up in {time.time() - t0:.1f}s")
+    for L in layers:
+        log(f"[bench]   {L.spec.name}: {L.plan}")
+
+    stream = torch.cuda.current_stream()
+
+    if args.only:
+        for L in layers:
+            for _ in range(args.warmup + args.steps):
+                if args.only == "dw":
+                    B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], stream)
+                elif args.only == "compress":
+                    B.cac_compress(L.d, L.X, L.Z, stream)
+                elif args.only == "fwd":
+                    B.conv_fwd_and_compress(L.d, L.X, L.W, L.b, L.Y, L.Z, L.ws[B.OP_FWD_AND_COMPRESS], stream)
+                else:
+                    B.conv_bwd_data(L.d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "workload": args.workload, "calls_per_layer": args.warmup + args.steps}))
+        return
+
+    def step():
+        for L in layers:
+            B.conv_fwd_and_compress(L.d, L.X, L.W, L.b, L.Y, L.Z, L.ws[B.OP_FWD_AND_COMPRESS], stream)
+            B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], stream)
+            B.conv_bwd_data(L.d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], stream)
+
+    # ---- untimed warm-up (also sets kernel attributes before any capture)
+    for _ in range(max(1, args.warmup)):
+        step()
+    torch.cuda.synchronize()
+
+    graph = None
+    if not args.no_graph:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                stream = side
+                step()
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step()
+            torch.cuda.synchronize()
+            ref = [L.dW.clone() for L in layers]
+            for _ in range(3):
+                g.replay()
+            torch.cuda.synchronize()
+            assert all(torch.equal(r, L.dW) for r, L in zip(ref, layers)), "graph replay changed dW"
+            graph = g
+        except Exception as e:  # capture is an optimisation of the launch path only
+            log(f"[bench] HIP graph capture unavailable ({type(e).__name__}: {e}); launching eagerly")
+            graph = None
+        stream = torch.cuda.current_stream()
+
+    run = (lambda: graph.replay()) if graph is not None else step
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # ---- per-op durations with events on the launch stream (instrumented loop, eager)
+    nrep = max(5, min(args.steps, 30))
+    names = ("fwd+compress", "dw", "dx")
+    acc = {n: [0.0] * len(layers) for n in names}
+    evs = []
+    for _ in range(nrep):
+        for i, L in enumerate(layers):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            e[0].record(stream)
+            B.conv_fwd_and_compress(L.d, L.X, L.W, L.b, L.Y, L.Z, L.ws[B.OP_FWD_AND_COMPRESS], stream)
+            e[1].record(stream)
+            B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], stream)
+            e[2].record(stream)
+            B.conv_bwd_data(L.d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], stream)
+            e[3].record(stream)
+            evs.append((i, e))
+    torch.cuda.synchronize()
+    for i, e in evs:
+        for j, n in enumerate(names):
+            acc[n][i] += e[j].elapsed_time(e[j + 1]) / nrep  # ms
+
+    # ---- compress alone: warm (same buffers) and cold (rotating through > 512 MiB)
+    comp = []
+    for L in layers:
+        es = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for _ in range(5):
+            B.cac_compress(L.d, L.X, L.Z, stream)
+        es[0].record(stream)
+        for _ in range(50):
+            B.cac_compress(L.d, L.X, L.Z, stream)
+        es[1].record(stream)
+        torch.cuda.synchronize()
+        warm_ms = es[0].elapsed_time(es[1]) / 50
+        ncopy = max(2, int((640 << 20) // max(L.x_bytes, 1)) + 1)
+        ncopy = min(ncopy, 64)
+        xs = [L.X.clone() for _ in range(ncopy)]
+        for x in xs:
+            B.cac_compress(L.d, x, L.Z, stream)
+        es = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        es[0].record(stream)
+        reps = 3
+        for _ in range(reps):
+            for x in xs:
+                B.cac_compress(L.d, x, L.Z, stream)
+        es[1].record(stream)
+        torch.cuda.synchronize()
+        cold_ms = es[0].elapsed_time(es[1]) / (reps * ncopy)
+        del xs
+        comp.append((warm_ms, cold_ms))
+
+    # ---- report
+    tot_flops = sum(sum(L.flops.values()) for L in layers)
+    dw_flops = sum(L.flops["dw"] for L in layers)
+    dw_ms = sum(acc["dw"])
+    log(f"[bench] {'layer':28s} {'fwd+cmp us':>10s} {'dW us':>8s} {'dW TF/s':>8s} {'%peak':>6s} {'dX us':>8s} "
+        f"{'cmp cold GB/s':>13s} {'%hbm':>5s} {'warm GB/s':>9s} {'X MiB':>7s} {'Z MiB':>7s} {'saved':>6s}")
+    per_layer = []
+    for i, L in enumerate(layers):
+        dw_tf = L.flops["dw"] / (acc["dw"][i] * 1e-3) / 1e12
+        warm, cold = comp[i]
+        cg, wg = L.bytes["compress"] / (cold * 1e-3) / 1e9, L.bytes["compress"] / (warm * 1e-3) / 1e9
+        log(f"[bench] {L.spec.name:28s} {acc['fwd+compress'][i] * 1e3:10.1f} {acc['dw'][i] * 1e3:8.1f} {dw_tf:8.1f} "
+            f"{100 * dw_tf / PEAK_BF16_TFLOPS:6.1f} {acc['dx'][i] * 1e3:8.1f} {cg:13.0f} {100 * cg / PEAK_HBM_GBPS:5.1f} "
+            f"{wg:9.0f} {L.x_bytes / 2**20:7.2f} {L.z_bytes / 2**20:7.2f} {L.x_bytes / L.z_bytes:6.2f}")
+        per_layer.append({"layer": L.spec.name, "dw_us": round(acc["dw"][i] * 1e3, 2), "dw_tflops": round(dw_tf, 1),
+                          "fwd_compress_us": round(acc["fwd+compress"][i] * 1e3, 2), "dx_us": round(acc["dx"][i] * 1e3, 2),
+                          "compress_cold_gbps": round(cg, 1), "compress_warm_gbps": round(wg, 1),
+                          "x_bytes": L.x_bytes, "z_bytes": L.z_bytes})
+    dw_tflops = dw_flops / (dw_ms * 1e-3) / 1e12
+    comp_bytes = sum(L.bytes["compress"] for L in layers)
+    comp_cold_gbps = comp_bytes / (sum(c for _, c in comp) * 1e-3) / 1e9
+    x_total, z_total = sum(L.x_bytes for L in layers), sum(L.z_bytes for L in layers)
+
+    out = {
+        "metric": "dW TFLOP/s + compress GB/s (% of MI355X roofline); activation bytes saved",
+        "value": round(tot_flops / (ms_per_step * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s (fwd + dW-from-Z + dX algorithmic flops of one step / step time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if specs[0].dtype == synth.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": [L.spec.name for L in layers], "batch": specs[0].N,
+                   "pool_k": specs[0].k, "launch": "hip_graph" if graph is not None else "eager"},
+        "dw_tflops": round(dw_tflops, 1), "dw_frac_of_bf16_peak": round(dw_tflops / PEAK_BF16_TFLOPS, 4),
+        "compress_cold_gbps": round(comp_cold_gbps, 1), "compress_frac_of_hbm_peak": round(comp_cold_gbps / PEAK_HBM_GBPS, 4),
+        "activation_bytes": {"x": x_total, "z": z_total, "saved": x_total - z_total, "ratio": round(x_total / z_total, 3)},
+        "roofline": {"kernel": "dw_mfma_kernel (+ slice reduction) via conv_bwd_weight_compressed", "bound": "mfma",
+                     "achieved": round(dw_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(dw_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "flops_per_launch": dw_flops // len(layers), "avg_launch_us": round(dw_ms * 1e3 / len(layers), 2)},
+        "per_layer": per_layer,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers[0], args.cpu_seconds, np)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(L, seconds, np):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample:
+    pooling + inflation of the whole activation of the first layer, then as many
+    dW entries (full reduction length each) as fit the time budget."""
+    import oracle
+    spec = L.spec
+    g = oracle.ConvGeom(spec.N, spec.C, spec.K, spec.H, spec.W, spec.R, spec.S, spec.stride, spec.stride,
+                        spec.pad, spec.pad)
+    X, dY = L.host["X"].astype(np.float64), L.host["dY"].astype(np.float64)
+    t0 = time.perf_counter()
+    Xh = oracle.inflate(oracle.avgpool(X, spec.k, spec.k), spec.H, spec.W, spec.k, spec.k)
+    t_pool = time.perf_counter() - t0
+    total = spec.K * spec.C * spec.R * spec.S
+    rng = np.random.Generator(np.random.Philox(key=5))
+    probe = rng.integers(0, total, 256)
+    t0 = time.perf_counter()
+    oracle.conv_dw_entries(g, Xh, dY, probe)
+    t_probe = time.perf_counter() - t0
+    n = int(min(total, max(256, 256 * seconds / max(t_probe, 1e-6))))
+    idx = rng.integers(0, total, n)
+    t0 = time.perf_counter()
+    oracle.conv_dw_entries(g, Xh, dY, idx)
+    t_dw = time.perf_counter() - t0
+    flops = 2.0 * n * spec.N * spec.P * spec.Q
+    return {"value": round(flops / t_dw / 1e12, 5), "unit": "TFLOP/s (dW entries, fp64 direct loops)",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n} of {total} dW entries of layer {spec.name} at full reduction length "
+                      f"({t_dw:.1f}s; whole-layer dW extrapolates linearly to {t_dw * total / n:.0f}s); "
+                      f"pool+inflate of the whole activation {t_pool:.2f}s"}
+
+
+if __name__ == "__main__":
+    main()

@@ -166,3 +166,25 @@ def conv_bwd_data(d, W, dY, dX, ws=None, stream=None):
 
 def conv_bwd_bias(d, dY, db, stream=None):
     _check(lib().conv_bwd_bias(ctypes.byref(d), _ptr(dY), _ptr(db), _stream(stream)))
+
+
+# ---- host <-> device marshalling (type conversion only, no arithmetic)
+
+def to_device(a, dtype: str, device: str = "cuda:0"):
+    """float32 host array already rounded to `dtype` -> device tensor of that dtype."""
+    import numpy as np
+    import torch
+    if dtype == synth.F32:
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    bits = synth.bf16_bits(a).view(np.int16)
+    return torch.from_numpy(bits).to(device).view(torch.bfloat16)
+
+
+def to_host(t):
+    """device tensor -> float64 host array (bfloat16 widened exactly)."""
+    import numpy as np
+    import torch
+    if t.dtype == torch.bfloat16:
+        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return synth.bf16_from_bits(bits).astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)

@@ -7,21 +7,33 @@
 //                                             replication)
 //
 // GEMM view: M = output channels o, N = (input channel c, filter tap), K = pixels.
-// A workgroup (4 waves, 2x2) owns a 64 (o) x 64 (c) x all-taps tile and a slice
-// of the pixels; each wave a 32 x 32 x taps tile, i.e. one 32x32 accumulator
-// block per tap.  The pixel dimension is walked in "segments" of 8 consecutive
-// output pixels of one output row: a 32x32x16 MFMA consumes two segments, one in
-// lanes 0-31 and one in lanes 32-63 (rows rho and rho+1 of the staged chunk).
+// A workgroup of WM x WN waves owns a (32*MI*WM) x (32*NI*WN) x all-taps tile and
+// a slice of the pixels; each wave MI x NI x taps accumulator blocks of 32x32,
+// one wave per SIMD.
 //
-// Staging per chunk (NBI images x PR output rows):
-//   sDY [64 o][LR rows][Qpad]      dY, rows padded with zeros to a multiple of 8
-//   sX  [64 c][slots][XW]          the needed rows of Z, expanded along the row
-//                                  to full input width (xhat rows), zeros past W;
-//                                  the last slot is an all-zero row
-// The inflated activation exists only here: expanded horizontally when written
-// to LDS, expanded vertically by mapping an input row h to the slot of Z row
-// h/kh.  The filter taps along the row are produced in registers by shifting a
-// sliding window of xhat blocks with v_perm.
+// The pixel sum is re-indexed by the xhat column instead of the output column:
+// with s - PAD = SG*a_s + b_s (0 <= b_s < SG),
+//   dW[o,c,r,s] = sum_{n,p,j} dY[n,o,p,j-a_s] * xhat[n,c,p*SG+r-PAD, SG*j+b_s]
+// so the xhat operand is always an ALIGNED block of 8 columns of "phase" b_s of
+// an xhat row (phase b holds columns b, b+SG, ...), and only the dY operand is
+// shifted (by a_s = -1, 0 or +1 columns).  One shifted dY fragment serves all
+// filter rows and input-channel blocks; it is made in registers with v_perm from
+// a sliding window over the dY row.  Zero padding needs no halo: columns outside
+// the image simply do not occur, pixels outside the row are zero in the window.
+// A 32x32x16 MFMA consumes two such blocks of 8, one in lanes 0-31 and one in
+// lanes 32-63 (rows rho and rho+1 of the staged chunk).
+//
+// Staging per chunk (NBI images x PR output rows), double buffered in LDS:
+//   rows [LR]                      per row: LDS offsets of its dY row and of the
+//                                  xhat rows feeding each filter row
+//   sDY  [tile_o][LR rows][Qpad]   dY, rows padded with zeros to a multiple of 8
+//   sX   [tile_c][slots][phase][Qpad]  the needed rows of Z, expanded along the
+//                                  row to full input width, zeros past W
+// plus one shared all-zero row.  The inflated activation exists only here:
+// expanded horizontally when written to LDS, expanded vertically by mapping an
+// input row h to the slot of Z row h/kh.
+#include <stdlib.h>
+
 #include "common.h"
 #include "dw_mfma.h"
 
@@ -45,8 +57,8 @@ template <int ha, int hb> __device__ __forceinline__ uint32_t halves(uint32_t a,
     return __builtin_amdgcn_perm(b, a, sel);
 }
 
-constexpr int kMaxDy = 4; // 16-byte dY items a thread moves per chunk
-constexpr int kMaxZ = 8;  // 8-byte Z items a thread moves per chunk
+constexpr int kMaxDy = 8; // 16-byte dY items a thread moves per chunk
+constexpr int kMaxZ = 4;  // 16-byte Z items a thread moves per chunk
 
 // A window of one xhat row held in registers: the last dword of the block left
 // of the current position and NB blocks starting at it.
@@ -55,8 +67,7 @@ template <int NB> struct Window {
     u32x4 blk[NB];
 };
 
-// Element `e` (relative to the first element of blk[0]; -2 <= e < 8*NB) as
-// (register, half).
+// Element `e` (relative to the first element of blk[0]; -2 <= e < 8*NB): its register.
 template <int NB, int e> __device__ __forceinline__ uint32_t win_reg(const Window<NB> &w)
 {
     static_assert(e >= -2 && e < 8 * NB, "window too small");
@@ -72,74 +83,88 @@ template <int e> constexpr int win_half() { return ((e % 2) + 2) % 2; }
 template <int NB, int SG, int PAD, int s> __device__ __forceinline__ bf16x8 make_frag(const Window<NB> &w)
 {
     union { u32x4 u; bf16x8 v; } f;
-#define CAC_FRAG_DWORD(i)                                                                        \
-    {                                                                                            \
-        constexpr int e0 = SG * (2 * i) + s - PAD, e1 = SG * (2 * i + 1) + s - PAD;              \
-        f.u[i] = halves<win_half<e0>(), win_half<e1>()>(win_reg<NB, e0>(w), win_reg<NB, e1>(w)); \
+#define CAC_FRAG_DWORD(i)                                                                            \
+    {                                                                                                \
+        constexpr int e0 = SG * (2 * i) + s - PAD, e1 = SG * (2 * i + 1) + s - PAD;                  \
+        if constexpr (e0 >= 0 && e0 % 2 == 0 && e1 == e0 + 1)                                        \
+            f.u[i] = win_reg<NB, e0>(w); /* both halves of one dword, in place */                    \
+        else                                                                                         \
+            f.u[i] = halves<win_half<e0>(), win_half<e1>()>(win_reg<NB, e0>(w), win_reg<NB, e1>(w)); \
     }
     CAC_FRAG_DWORD(0) CAC_FRAG_DWORD(1) CAC_FRAG_DWORD(2) CAC_FRAG_DWORD(3)
 #undef CAC_FRAG_DWORD
     return f.v;
 }
 
-// 8 consecutive bf16 starting at src, of which only the first `left` exist;
-// VEC = widest vector the address is aligned for.
-template <int VEC> __device__ __forceinline__ u32x4 load8(const bf16_t *src, int left)
+// Global reads go through buffer loads: a lane whose byte offset is kNoLoad (or
+// anything at or beyond the tensor's size) gets zeros back without touching
+// memory and without a branch, so every load of a chunk can be in flight at once.
+constexpr uint32_t kNoLoad = 0x80000000u; // tensors on this path are smaller than 2 GiB
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
-    u32x4 v = {0, 0, 0, 0};
-    if constexpr (VEC == 8) {
-        v = *(const u32x4 *)src;
-    } else if constexpr (VEC == 4) {
-        u32x2 a = *(const u32x2 *)src, b = {0, 0};
-        if (left > 4) b = *(const u32x2 *)(src + 4);
-        v = u32x4{a[0], a[1], b[0], b[1]};
-    } else if constexpr (VEC == 2) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (left > 2 * j) v[j] = *(const uint32_t *)(src + 2 * j);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t lo = left > 2 * j ? src[2 * j] : 0, hi = left > 2 * j + 1 ? src[2 * j + 1] : 0;
-            v[j] = pack16(lo, hi);
-        }
-    }
-    return v;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
 }
 
-template <int VEC> __device__ __forceinline__ u32x2 load4(const bf16_t *src, int left)
+// 8 consecutive bf16 starting at ELEMENT offset e of a tensor, as they arrive:
+// the 4 dwords from the dword-aligned address down from it (rows of odd length
+// start on odd elements).  Always one 16-byte load.
+__device__ __forceinline__ u32x4 load_raw8(rsrc_t rs, uint32_t e, bool live)
 {
-    u32x2 v = {0, 0};
-    if constexpr (VEC == 4) {
-        v = *(const u32x2 *)src;
-    } else if constexpr (VEC == 2) {
-        v[0] = *(const uint32_t *)src;
-        if (left > 2) v[1] = *(const uint32_t *)(src + 2);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            uint32_t lo = left > 2 * j ? src[2 * j] : 0, hi = left > 2 * j + 1 ? src[2 * j + 1] : 0;
-            v[j] = pack16(lo, hi);
-        }
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, live ? (e & ~1u) * 2u : kNoLoad, 0, 0);
+}
+// The 8 elements themselves.  After an odd start everything moves down by one
+// element and the last one comes from the first dword of the next item of the
+// same row, which the next lane holds (the copy maps consecutive items of a row
+// to consecutive lanes; the last item of a row never needs it: a row of odd
+// length ends before its 8th element).  Then ANDed with `mask`: zero from the
+// row's end on, what follows belongs to another row.
+__device__ __forceinline__ u32x4 fix8(const u32x4 &d, uint32_t e, const u32x4 &mask, bool odd_possible)
+{
+    u32x4 v = d;
+    if (odd_possible) {
+        const uint32_t next0 = __shfl_down(d[0], 1, 64);
+        const uint32_t sh = (e & 1u) * 16u;
+        v[0] = __builtin_amdgcn_alignbit(d[1], d[0], sh);
+        v[1] = __builtin_amdgcn_alignbit(d[2], d[1], sh);
+        v[2] = __builtin_amdgcn_alignbit(d[3], d[2], sh);
+        v[3] = __builtin_amdgcn_alignbit(next0, d[3], sh);
     }
-    return v;
+    return v & mask;
+}
+// Dword j of the mask keeps the elements 2j, 2j+1 that lie below `left`.
+__device__ __forceinline__ u32x4 mask8(int left)
+{
+    u32x4 m;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int l2 = left - 2 * j;
+        m[j] = l2 >= 2 ? 0xffffffffu : (l2 == 1 ? 0xffffu : 0u);
+    }
+    return m;
 }
 
-template <int R, int S, int SG, int PAD>
-__global__ void __launch_bounds__(256, 2) dw_mfma_kernel(DwMfmaParams p)
+template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN>
+__global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
 {
     constexpr int T = R * S;
-    // blocks of 8 xhat elements a segment touches, counted from block SG*seg
-    constexpr int NB = (7 * SG + S - 1 - PAD) / 8 + 1;
-    static_assert(PAD <= 2 && SG <= NB, "unsupported filter geometry");
+    constexpr int NT = 64 * WM * WN; // threads of each kind: MFMA waves, then as many copy waves
+    constexpr int TILE_O = 32 * MI * WM, TILE_C = 32 * NI * WN;
+    // floor division / remainder of (s - PAD) by SG for every filter column
+    constexpr auto a_of = [](int s) { int d = s - PAD; return d >= 0 ? d / SG : -((-d + SG - 1) / SG); };
+    constexpr auto b_of = [](int s) { int d = s - PAD; return d - SG * (d >= 0 ? d / SG : -((-d + SG - 1) / SG)); };
+    constexpr int NPH = (S == 1) ? 1 : SG; // xhat column phases in use
+    static_assert(S <= 3 && SG <= 2 && a_of(0) >= -1 && a_of(S - 1) <= 1, "unsupported filter geometry");
 
     extern __shared__ __align__(16) unsigned char smem[];
-    // [zero row][buffer 0: sDY, sX][buffer 1: sDY, sX]
-    const bf16_t *sZero = (const bf16_t *)smem;
-    bf16_t *sBuf = (bf16_t *)smem + p.XW;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1, half = lane >> 5, l32 = lane & 31;
+    // [zero row][buffer 0: rows, sDY, sX][buffer 1: rows, sDY, sX]; offsets below are in
+    // bf16 elements from the start of LDS, so offset 0 is the zero row
+    const bf16_t *sBase = (const bf16_t *)smem;
+    bf16_t *sW = (bf16_t *)smem;
+    const uint32_t rows_elems = p.LRpad * 8;                   // one 16-byte entry per row
+    const uint32_t buf_elems = rows_elems + TILE_O * p.dy_ostride + TILE_C * p.x_cstride;
+    const uint32_t slot_w = NPH * p.PW;                        // one xhat row: all phases
+    const uint32_t base0 = slot_w, base1 = base0 + buf_elems;  // the buffers follow the zero row
 
     // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that each
     // XCD works on consecutive (slice, o-tile, c-tile) triples and re-reads of dY
@@ -150,256 +175,462 @@ __global__ void __launch_bounds__(256, 2) dw_mfma_kernel(DwMfmaParams p)
     const int ntiles = p.tiles_o * p.tiles_c;
     const int slice = v / ntiles, tile = v - slice * ntiles;
     const int ot = tile / p.tiles_c, ct = tile - ot * p.tiles_c;
-    const int o0 = ot * 64, c0 = ct * 64;
+    const int o0 = ot * TILE_O, c0 = ct * TILE_C;
 
     // Everything in LDS starts finite (zero): pad columns, the spare row of an odd
     // chunk and the zero row are multiplied with something in every MFMA.
-    for (int i = tid; i < p.lds_bytes / 16; i += 256) ((u32x4 *)smem)[i] = u32x4{0, 0, 0, 0};
+    for (int i = threadIdx.x; i < p.lds_bytes / 16; i += 2 * NT) ((u32x4 *)smem)[i] = u32x4{0, 0, 0, 0};
+    __syncthreads();
 
     const int ci_begin = slice * p.chunks_per_slice;
     const int ci_end = min(ci_begin + p.chunks_per_slice, p.nchunks);
 
-    // ---- what this thread copies, fixed for the whole kernel ----------------------
-    // dY: LDY lanes share one output channel's rows; item j = (row rho, segment sg)
-    const uint32_t dyj = tid & (p.LDY - 1), dyo = tid >> p.ldy_log2;
-    const uint32_t dy_rho = fdiv(dyj, p.m_segs), dy_sg = dyj - dy_rho * p.SEGS;
-    const uint32_t dy_ni = fdiv(dy_rho, p.m_pr), dy_pr = dy_rho - dy_ni * p.PR;
-    const bool dy_write = dyj < (uint32_t)p.rowitems;             // lanes past the row's items idle
-    const bool dy_real = dy_write && dy_rho < (uint32_t)p.LR;     // the spare row stays zero
-    const int dy_left = p.Q - (int)dy_sg * 8;
-    const uint32_t dy_rel = ((dy_ni * p.K + dyo) * p.P + dy_pr) * p.Q + dy_sg * 8;
-    const uint32_t dy_gstep = (256u >> p.ldy_log2) * p.P * p.Q;   // next pass: 256/LDY channels on
-    const uint32_t dy_lds = dyo * p.dy_ostride + dyj * 8;
-    const uint32_t dy_lstep = (256u >> p.ldy_log2) * p.dy_ostride;
-    // Z: LPC lanes share one input channel; item j = (image ni, slot sl, vector zv)
-    const uint32_t zj = tid & (p.LPC - 1), zc = tid >> p.lpc_log2;
-    const uint32_t z_row = fdiv(zj, p.m_zv), z_zv = zj - z_row * p.ZV;
-    const uint32_t z_ni = fdiv(z_row, p.m_nz), z_sl = z_row - z_ni * p.NZ;
-    const bool z_write = zj < (uint32_t)p.citems;
-    const int z_left = p.Wp - (int)z_zv * 4;
-    const uint32_t z_rel = ((z_ni * p.C + zc) * p.Hp + z_sl) * p.Wp + z_zv * 4;
-    const uint32_t z_gstep = (256u >> p.lpc_log2) * p.Hp * p.Wp;
-    const uint32_t z_lds = zc * p.x_cstride + z_row * p.XW + ((z_zv * 4) << p.kw_log2);
-    const uint32_t z_lstep = (256u >> p.lpc_log2) * p.x_cstride;
-    const int z_col0 = (int)(z_zv * 4) << p.kw_log2;              // first xhat column of the item
+    // the role of a wave is uniform over the wave: tell the compiler so
+    const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wave_id >= NT / 64) {
+        // =========================== copy waves ===========================================
+        // They keep two chunks of global loads in flight and fill the LDS buffer the
+        // MFMA waves are not reading; the only hand-over is one barrier per chunk.
+        const int tid = threadIdx.x - NT;
+        // dY: LDY lanes share one output channel's rows; item j = (row rho, segment sg)
+        const uint32_t dyj = tid & (p.LDY - 1), dyo = tid >> p.ldy_log2;
+        const uint32_t dy_rho = fdiv(dyj, p.m_segs), dy_sg = dyj - dy_rho * p.SEGS;
+        const uint32_t dy_ni = fdiv(dy_rho, p.m_pr), dy_pr = dy_rho - dy_ni * p.PR;
+        const bool dy_write = dyj < (uint32_t)p.rowitems;         // lanes past the row's items idle
+        const bool dy_real = dy_write && dy_rho < (uint32_t)p.LR; // the spare row stays zero
+        const u32x4 dy_mask = mask8(p.Q - (int)dy_sg * 8);
+        const uint32_t dy_rel = ((dy_ni * p.K + dyo) * p.P + dy_pr) * p.Q + dy_sg * 8;
+        const uint32_t dy_opp = (uint32_t)NT >> p.ldy_log2;       // output channels per pass
+        const uint32_t dy_gstep = dy_opp * p.P * p.Q;
+        const uint32_t dy_lds = rows_elems + dyo * p.dy_ostride + dyj * 8;
+        const uint32_t dy_lstep = dy_opp * p.dy_ostride;
+        // Z: LPC lanes share one input channel; item j = (image ni, slot sl, vector zv of 8 pooled values)
+        const uint32_t zj = tid & (p.LPC - 1), zc = tid >> p.lpc_log2;
+        const uint32_t z_row = fdiv(zj, p.m_zv), z_zv = zj - z_row * p.ZV;
+        const uint32_t z_ni = fdiv(z_row, p.m_nz), z_sl = z_row - z_ni * p.NZ;
+        const bool z_write = zj < (uint32_t)p.citems;
+        const u32x4 z_mask = mask8(p.Wp - (int)z_zv * 8);
+        const uint32_t z_rel = ((z_ni * p.C + zc) * p.Hp + z_sl) * p.Wp + z_zv * 8;
+        const uint32_t z_cpp = (uint32_t)NT >> p.lpc_log2;        // input channels per pass
+        const uint32_t z_gstep = z_cpp * p.Hp * p.Wp;
+        const uint32_t z_lds = rows_elems + TILE_O * p.dy_ostride + zc * p.x_cstride + z_row * slot_w;
+        const uint32_t z_lstep = z_cpp * p.x_cstride;
+        const bool dy_odd = p.Q & 1, z_odd = p.Wp & 1;
+        const int f_log2 = p.kw_log2 - (SG == 2 ? 1 : 0);        // columns of one phase per pooled value, log2
+        const bool ragged = (p.W & ((1 << p.kw_log2) - 1)) != 0; // the last pooling tile reaches past W
+        const rsrc_t rs_dy = make_rsrc(p.dY, (uint32_t)p.N * p.K * p.P * p.Q * 2u);
+        const rsrc_t rs_z = make_rsrc(p.Z, (uint32_t)p.N * p.C * p.Hp * p.Wp * 2u);
+        const int olim = p.K - o0 - (int)dyo; // pass i holds a real output channel when i*opp < olim
+        const int clim = p.C - c0 - (int)zc;
 
-    u32x4 pre_dy[kMaxDy];
-    u32x2 pre_z[kMaxZ];
-
-    // ---- global -> registers for one chunk ----------------------------------------
-    auto prefetch = [&](int ci) {
-        const int ig = ci / p.RB, rb = ci - ig * p.RB;
-        const int n0 = ig * p.NBI, p0 = rb * p.PR;
-        const int zbase = max(0, (p0 * SG - PAD) >> p.kh_log2);
-        {
-            const bool ok = dy_real && n0 + (int)dy_ni < p.N && p0 + (int)dy_pr < p.P;
-            const bf16_t *src = p.dY + ((uint32_t)(n0 * p.K + o0) * p.P + p0) * p.Q + dy_rel;
-            const int olim = p.K - o0 - (int)dyo; // passes with i*OPP < olim are real channels
-#define CAC_DY_PASSES(VEC)                                                                        \
-    _Pragma("unroll") for (int i = 0; i < kMaxDy; ++i)                                            \
-    {                                                                                             \
-        u32x4 val = {0, 0, 0, 0};                                                                 \
-        if (i < p.dy_passes && ok && (i << (8 - p.ldy_log2)) < olim) val = load8<VEC>(src + i * dy_gstep, dy_left); \
-        pre_dy[i] = val;                                                                          \
-    }
-            if (p.dy_vec == 8) { CAC_DY_PASSES(8) }
-            else if (p.dy_vec == 4) { CAC_DY_PASSES(4) }
-            else if (p.dy_vec == 2) { CAC_DY_PASSES(2) }
-            else { CAC_DY_PASSES(1) }
-#undef CAC_DY_PASSES
-        }
-        {
-            const bool ok = z_write && n0 + (int)z_ni < p.N && zbase + (int)z_sl < p.Hp;
-            const bf16_t *src = p.Z + ((uint32_t)(n0 * p.C + c0) * p.Hp + zbase) * p.Wp + z_rel;
-            const int clim = p.C - c0 - (int)zc;
-#define CAC_Z_PASSES(VEC)                                                                         \
-    _Pragma("unroll") for (int i = 0; i < kMaxZ; ++i)                                             \
-    {                                                                                             \
-        u32x2 val = {0, 0};                                                                       \
-        if (i < p.z_passes && ok && (i << (8 - p.lpc_log2)) < clim) val = load4<VEC>(src + i * z_gstep, z_left); \
-        pre_z[i] = val;                                                                           \
-    }
-            if (p.z_vec == 4) { CAC_Z_PASSES(4) }
-            else if (p.z_vec == 2) { CAC_Z_PASSES(2) }
-            else { CAC_Z_PASSES(1) }
-#undef CAC_Z_PASSES
-        }
-    };
-
-    // ---- registers -> LDS buffer (with the horizontal inflation) --------------------
-    auto stage = [&](bf16_t *sDY, bf16_t *sX) {
-        if (dy_write) {
+        // element offsets of this thread's first dY / Z item of chunk ci, and whether it exists
+        struct Src { uint32_t dy, z; bool dy_ok, z_ok; int zbase, n0, p0; };
+        auto src_of = [&](int ci) {
+            Src s;
+            const int ig = ci / p.RB, rb = ci - ig * p.RB;
+            s.n0 = ig * p.NBI;
+            s.p0 = rb * p.PR;
+            s.zbase = max(0, (s.p0 * SG - PAD) >> p.kh_log2);
+            s.dy_ok = dy_real && s.n0 + (int)dy_ni < p.N && s.p0 + (int)dy_pr < p.P;
+            s.dy = ((uint32_t)(s.n0 * p.K + o0) * p.P + s.p0) * p.Q + dy_rel;
+            s.z_ok = z_write && s.n0 + (int)z_ni < p.N && s.zbase + (int)z_sl < p.Hp;
+            s.z = ((uint32_t)(s.n0 * p.C + c0) * p.Hp + s.zbase) * p.Wp + z_rel;
+            return s;
+        };
+        // ---- global -> registers for one chunk
+        auto fetch = [&](int ci, u32x4 (&rdy)[kMaxDy], u32x4 (&rz)[kMaxZ]) {
+            const Src s = src_of(ci);
 #pragma unroll
             for (int i = 0; i < kMaxDy; ++i)
-                if (i < p.dy_passes) *(u32x4 *)(sDY + dy_lds + i * dy_lstep) = pre_dy[i];
-        }
-        if (z_write) {
+                rdy[i] = load_raw8(rs_dy, s.dy + i * dy_gstep, i < p.dy_passes && s.dy_ok && (int)(i * dy_opp) < olim);
 #pragma unroll
-            for (int i = 0; i < kMaxZ; ++i) {
-                if (i < p.z_passes) {
-                    const u32x2 z = pre_z[i];
-                    bf16_t *dst = sX + z_lds + i * z_lstep;
-                    // pooled value e of the vector, in both halves of a dword
-                    const uint32_t d0 = halves<0, 0>(z[0], z[0]), d1 = halves<1, 1>(z[0], z[0]);
-                    const uint32_t d2 = halves<0, 0>(z[1], z[1]), d3 = halves<1, 1>(z[1], z[1]);
-                    // columns at or beyond W are zero (a ragged last pooling tile reaches past W)
-                    auto put = [&](int off, u32x4 x) {
-                        const int left = p.W - z_col0 - off;
+            for (int i = 0; i < kMaxZ; ++i)
+                rz[i] = load_raw8(rs_z, s.z + i * z_gstep, i < p.z_passes && s.z_ok && (int)(i * z_cpp) < clim);
+        };
+        // ---- registers -> LDS buffer at element offset `base` (with the horizontal inflation)
+        auto stage = [&](int ci, uint32_t base, const u32x4 (&rdy)[kMaxDy], const u32x4 (&rz)[kMaxZ]) {
+            const Src s = src_of(ci);
+            // row table: entry rho = {dY row offset, xhat row offset per filter row (the zero
+            // slot for rows outside the image)}, in elements from the lane's channel base
+            if (tid < p.LRpad) {
+                const uint32_t rho = tid;
+                const uint32_t ni = fdiv(rho, p.m_pr);
+                const int pp = s.p0 + (int)(rho - ni * p.PR);
+                const bool row_ok = rho < (uint32_t)p.LR && pp < p.P && s.n0 + (int)ni < p.N;
+                const uint32_t zero_slot = p.NBI * p.NZ * slot_w; // each channel ends with an all-zero xhat row
+                u32x4 e = {rho * (uint32_t)p.Qpad, zero_slot, zero_slot, zero_slot};
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            if (left <= 2 * j) x[j] = 0;
-                            else if (left == 2 * j + 1) x[j] &= 0xffffu;
-                        }
-                        *(u32x4 *)(dst + off) = x;
-                    };
-                    if (p.kw_log2 == 0) {
-                        *(u32x2 *)dst = z; // no horizontal inflation; zeros past W come from the load
-                    } else if (p.kw_log2 == 1) {
-                        put(0, u32x4{d0, d1, d2, d3});
-                    } else if (p.kw_log2 == 2) {
-                        put(0, u32x4{d0, d0, d1, d1});
-                        put(8, u32x4{d2, d2, d3, d3});
-                    } else {
-                        put(0, u32x4{d0, d0, d0, d0});
-                        put(8, u32x4{d1, d1, d1, d1});
-                        put(16, u32x4{d2, d2, d2, d2});
-                        put(24, u32x4{d3, d3, d3, d3});
-                    }
+                for (int r = 0; r < R; ++r) {
+                    const int h = pp * SG + r - PAD;
+                    const bool ok = row_ok && h >= 0 && h < p.H;
+                    e[1 + r] = ok ? ((int)ni * p.NZ + (h >> p.kh_log2) - s.zbase) * slot_w : zero_slot;
                 }
+                *(u32x4 *)(sW + base + rho * 8) = e;
             }
-        }
-    };
+#pragma unroll
+            for (int i = 0; i < kMaxDy; ++i)
+                if (i < p.dy_passes) { // (uniform; fix8 exchanges data between lanes)
+                    const u32x4 val = fix8(rdy[i], s.dy + i * dy_gstep, dy_mask, dy_odd);
+                    if (dy_write) *(u32x4 *)(sW + base + dy_lds + i * dy_lstep) = val;
+                }
+            {
+                // Writes 8 elements of phase ph starting at element j; in the ragged case the
+                // elements whose xhat column SG*j+ph is at or beyond W are zeroed.
+                auto put8 = [&](bf16_t *dst, int ph, int j, u32x4 x) {
+                    if (ragged) x &= mask8((p.W - ph + SG - 1) / SG - j);
+                    if (z_write) *(u32x4 *)(dst + ph * p.PW + j) = x;
+                };
+#define CAC_Z_ITEMS(...)                                                                           \
+    _Pragma("unroll") for (int i = 0; i < kMaxZ; ++i) if (i < p.z_passes)                          \
+    {                                                                                              \
+        const u32x4 z = fix8(rz[i], s.z + i * z_gstep, z_mask, z_odd);                             \
+        bf16_t *dst = sW + base + z_lds + i * z_lstep;                                             \
+        /* pooled value k of the item in both halves of a dword */                                 \
+        auto dup = [&](int k) { return (k & 1) ? halves<1, 1>(z[k >> 1], z[k >> 1]) : halves<0, 0>(z[k >> 1], z[k >> 1]); }; \
+        (void)dup;                                                                                 \
+        __VA_ARGS__                                                                                \
+    }
+                if (f_log2 < 0) {
+                    // kw = 1, stride 2: even columns to phase 0, odd ones to phase 1
+                    // (zeros past W come from the load)
+                    const int j0 = z_zv * 4;
+                    CAC_Z_ITEMS({
+                        if (z_write) *(u32x2 *)(dst + j0) = u32x2{halves<0, 0>(z[0], z[1]), halves<0, 0>(z[2], z[3])};
+                        if (z_write && NPH > 1)
+                            *(u32x2 *)(dst + p.PW + j0) = u32x2{halves<1, 1>(z[0], z[1]), halves<1, 1>(z[2], z[3])};
+                    })
+                } else if (f_log2 == 0) {
+                    const int j0 = z_zv * 8;
+                    CAC_Z_ITEMS({
+                        _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) put8(dst, ph, j0, z);
+                    })
+                } else if (f_log2 == 1) {
+                    const int j0 = z_zv * 16;
+                    CAC_Z_ITEMS({
+                        const u32x4 lo = {dup(0), dup(1), dup(2), dup(3)}, hi = {dup(4), dup(5), dup(6), dup(7)};
+                        _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) {
+                            put8(dst, ph, j0, lo);
+                            put8(dst, ph, j0 + 8, hi);
+                        }
+                    })
+                } else if (f_log2 == 2) {
+                    const int j0 = z_zv * 32;
+                    CAC_Z_ITEMS({
+                        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                            const u32x4 x = {dup(2 * g), dup(2 * g), dup(2 * g + 1), dup(2 * g + 1)};
+                            _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) put8(dst, ph, j0 + 8 * g, x);
+                        }
+                    })
+                } else {
+                    const int j0 = z_zv * 64;
+                    CAC_Z_ITEMS({
+                        _Pragma("unroll") for (int g = 0; g < 8; ++g) {
+                            const u32x4 x = {dup(g), dup(g), dup(g), dup(g)};
+                            _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) put8(dst, ph, j0 + 8 * g, x);
+                        }
+                    })
+                }
+#undef CAC_Z_ITEMS
+            }
+        };
 
-    f32x16 acc[T];
+        u32x4 dyA[kMaxDy], zA[kMaxZ], dyB[kMaxDy], zB[kMaxZ];
+        if (ci_begin < ci_end) {
+            fetch(ci_begin, dyA, zA);
+            if (ci_begin + 1 < ci_end) fetch(ci_begin + 1, dyB, zB);
+            stage(ci_begin, base0, dyA, zA);
+        }
+        __syncthreads(); // buffer 0 holds the first chunk
+        for (int ci = ci_begin; ci < ci_end; ci += 2) {
+            // MFMA waves are on buffer 0 (chunk ci); set B holds chunk ci+1
+            if (ci + 2 < ci_end) fetch(ci + 2, dyA, zA);
+            if (ci + 1 < ci_end) stage(ci + 1, base1, dyB, zB);
+            __syncthreads();
+            if (ci + 1 >= ci_end) break;
+            // MFMA waves are on buffer 1 (chunk ci+1); set A holds chunk ci+2
+            if (ci + 3 < ci_end) fetch(ci + 3, dyB, zB);
+            if (ci + 2 < ci_end) stage(ci + 2, base0, dyA, zA);
+            __syncthreads();
+        }
+        return;
+    }
+
+    // =============================== MFMA waves ===========================================
+    const int tid = threadIdx.x, lane = tid & 63, wave = wave_id;
+    const int wm = wave % WM, wn = wave / WM, half = lane >> 5, l32 = lane & 31;
+
+    f32x16 acc[MI][NI][T];
 #pragma unroll
-    for (int t = 0; t < T; ++t)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc[t][j] = 0.f;
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[mi][ni][t][j] = 0.f;
 
     // ---- MFMA over one staged chunk --------------------------------------------------
-    auto compute = [&](int ci, const bf16_t *sDY, const bf16_t *sX) {
-        const int ig = ci / p.RB, rb = ci - ig * p.RB;
-        const int n0 = ig * p.NBI, p0 = rb * p.PR;
-        const int zbase = max(0, (p0 * SG - PAD) >> p.kh_log2);
-        const bf16_t *xc = sX + (wn * 32 + l32) * p.x_cstride;
-        const bf16_t *ac = sDY + (wm * 32 + l32) * p.dy_ostride;
-        for (int rp = 0; rp < p.LRpad / 2; ++rp) {
-            const uint32_t rho = 2 * rp + half;
-            const uint32_t ni = fdiv(rho, p.m_pr);
-            const int pp = p0 + (int)(rho - ni * p.PR);
-            const bool row_ok = rho < (uint32_t)p.LR && pp < p.P && n0 + (int)ni < p.N;
-            const bf16_t *xrow[R];
+    // Operands of one step: the window over the dY row(s) and the xhat blocks.
+    struct Ops {
+        Window<2> aw[MI];
+        u32x4 b[R][NI][NPH];
+    };
+    // all MFMAs of one step: the window supplies the shifted dY fragments
+    auto mfma_step = [&](const Ops &o) {
+#define CAC_COL(s)                                                                                          \
+    if constexpr (s < S) {                                                                                  \
+        bf16x8 af[MI];                                                                                      \
+        _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) af[mi] = make_frag<2, 1, a_of(s), 0>(o.aw[mi]);   \
+        _Pragma("unroll") for (int r = 0; r < R; ++r)                                                       \
+        _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                                   \
+        {                                                                                                   \
+            union { u32x4 u; bf16x8 v; } bf;                                                                \
+            bf.u = o.b[r][ni][b_of(s)];                                                                     \
+            _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                                               \
+                acc[mi][ni][r * S + s] =                                                                    \
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bf.v, acc[mi][ni][r * S + s], 0, 0, 0); \
+        }                                                                                                   \
+    }
+        CAC_COL(1) CAC_COL(0) CAC_COL(2)
+#undef CAC_COL
+    };
+    // Interleaving hint for one step: after every MFMA one LDS read (while any are
+    // left) and a few VALU instructions, so that the next step's operand requests,
+    // the address arithmetic and the v_perm of the shifted fragments issue in the
+    // shadow of the MFMAs instead of between two steps (one MFMA wave per SIMD:
+    // nothing else would fill the gap).
+    auto interleave = [&]() {
+        constexpr int kMfma = MI * NI * T, kReads = MI * (S > 1 ? 2 : 1) + R * NI * NPH + 1;
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int h = pp * SG + r - PAD;
-                const bool ok = row_ok && h >= 0 && h < p.H;
-                xrow[r] = ok ? xc + ((int)ni * p.NZ + (h >> p.kh_log2) - zbase) * p.XW : sZero;
-            }
-            const bf16_t *arow = ac + rho * p.Qpad;
-            Window<NB> win[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                win[r].prev3 = 0;
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    win[r].blk[b] = b < p.XB ? *(const u32x4 *)(xrow[r] + 8 * b) : u32x4{0, 0, 0, 0};
-            }
-            for (int seg = 0; seg < p.SEGS; ++seg) {
-                union { u32x4 u; bf16x8 v; } a;
-                a.u = *(const u32x4 *)(arow + seg * 8);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-#define CAC_TAP(s)                                                                                       \
-    if constexpr (s < S)                                                                                 \
-        acc[r * S + s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, make_frag<NB, SG, PAD, s>(win[r]), \
-                                                                 acc[r * S + s], 0, 0, 0);
-                    CAC_TAP(0) CAC_TAP(1) CAC_TAP(2)
-#undef CAC_TAP
-                }
-                // slide every window SG blocks to the right
-                const int nxt = (seg + 1) * SG; // block index of the new blk[0]
-                const bool more = seg + 1 < p.SEGS;
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    win[r].prev3 = win[r].blk[SG - 1][3];
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        if (b + SG < NB)
-                            win[r].blk[b] = win[r].blk[b + SG];
-                        else
-                            win[r].blk[b] = (more && nxt + b < p.XB) ? *(const u32x4 *)(xrow[r] + 8 * (nxt + b))
-                                                                    : u32x4{0, 0, 0, 0};
-                    }
-                }
-            }
+        for (int i = 0; i < kMfma; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
+            if (i < kReads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);                 // VALU
         }
     };
+    // Requests the operands of segment `seg` of the rows at byte addresses ra / rx[]
+    // into `o`.  `tail`: the segment is the last of its row, nothing lies right of it.
+    const uint32_t astep = 64 * p.dy_ostride, xstep = 64 * p.x_cstride, pw = 2 * p.PW;
+    auto request = [&](Ops &o, uint32_t ra, const uint32_t (&rx)[R], int seg, bool tail) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            o.aw[mi].blk[0] = *(const u32x4 *)(smem + ra + mi * astep + 16 * seg);
+            if constexpr (S > 1) // byte 0 of LDS starts the zero row
+                o.aw[mi].blk[1] = *(const u32x4 *)(smem + (tail ? 0u : ra + mi * astep + 16 * seg + 16));
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int ph = 0; ph < NPH; ++ph)
+                    o.b[r][ni][ph] = *(const u32x4 *)(smem + rx[r] + ni * xstep + ph * pw + 16 * seg);
+    };
+    auto compute = [&](uint32_t base) {
+        // byte addresses in LDS of this lane's output channel / input channel
+        const uint32_t ac = 2 * (base + rows_elems + (wm * 32 * MI + l32) * p.dy_ostride);
+        const uint32_t xc = 2 * (base + rows_elems + TILE_O * p.dy_ostride + (wn * 32 * NI + l32) * p.x_cstride);
+        const uint32_t tab = 2 * base + half * 16; // row table, this half-wave's entries
+        const int nrp = p.LRpad / 2, segs = p.SEGS;
+        const int nsteps = nrp * segs;
 
-    // Double-buffered: while the MFMAs run on buffer b, the next chunk's global
-    // loads are in flight and are written to buffer b^1 afterwards; one barrier
-    // per chunk separates "all waves done reading b^1's previous content" from
-    // its refill and the refill from its use.
-    bf16_t *const sDY0 = sBuf, *const sX0 = sDY0 + 64 * p.dy_ostride;
-    bf16_t *const sDY1 = sX0 + 64 * p.x_cstride, *const sX1 = sDY1 + 64 * p.dy_ostride;
-    __syncthreads(); // zero fill done
-    if (ci_begin < ci_end) {
-        prefetch(ci_begin);
-        stage(sDY0, sX0);
+        // current rows of this lane and the raw table entry of the next row pair
+        u32x4 e = *(const u32x4 *)(smem + tab);
+        uint32_t ra = ac + 2 * e[0], rx[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e[1 + r];
+        u32x4 e_next = *(const u32x4 *)(smem + tab + 32 * min(1, nrp - 1));
+
+        Ops X, Y;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) X.aw[mi].prev3 = 0;
+        request(X, ra, rx, 0, segs == 1);
+
+        int seg = 0, rp = 0;
+        // One step: MFMAs on USE, operands of the following step requested into GET
+        // (same rows one segment to the right, or the next row pair, whose table
+        // entry was requested a row pair ago).
+#define CAC_STEP(USE, GET)                                                                        \
+    if (seg + 1 < segs) {                                                                         \
+        _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) GET.aw[mi].prev3 = USE.aw[mi].blk[0][3]; \
+        request(GET, ra, rx, seg + 1, seg + 2 == segs);                                           \
+        mfma_step(USE);                                                                           \
+        interleave();                                                                             \
+        ++seg;                                                                                    \
+    } else {                                                                                      \
+        ra = ac + 2 * e_next[0];                                                                  \
+        _Pragma("unroll") for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e_next[1 + r];             \
+        e_next = *(const u32x4 *)(smem + tab + 32 * min(rp + 2, nrp - 1));                        \
+        _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) GET.aw[mi].prev3 = 0;                   \
+        request(GET, ra, rx, 0, segs == 1);                                                       \
+        mfma_step(USE);                                                                           \
+        interleave();                                                                             \
+        seg = 0;                                                                                  \
+        ++rp;                                                                                     \
     }
-    __syncthreads();
-    int buf = 0;
-    for (int ci = ci_begin; ci < ci_end; ++ci, buf ^= 1) {
-        const bool more = ci + 1 < ci_end;
-        if (more) prefetch(ci + 1);
-        compute(ci, buf ? sDY1 : sDY0, buf ? sX1 : sX0);
-        if (more) stage(buf ? sDY0 : sDY1, buf ? sX0 : sX1);
+        for (int t = 0;;) {
+            CAC_STEP(X, Y)
+            if (++t == nsteps) break;
+            CAC_STEP(Y, X)
+            if (++t == nsteps) break;
+        }
+#undef CAC_STEP
+    };
+
+    __syncthreads(); // buffer 0 holds the first chunk
+    for (int ci = ci_begin; ci < ci_end; ci += 2) {
+        if (!(p.dbg & 2)) compute(base0);
+        __syncthreads();
+        if (ci + 1 >= ci_end) break;
+        if (!(p.dbg & 2)) compute(base1);
         __syncthreads();
     }
 
     // ---- epilogue --------------------------------------------------------------------
     // accumulator register j of lane l holds row 8*(j/4) + 4*(l/32) + j%4, column l%32
     if (p.direct) {
-        const int c = c0 + wn * 32 + l32;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int o = o0 + wm * 32 + 8 * (j / 4) + 4 * half + (j % 4);
-            if (o < p.K && c < p.C) {
-                float *dst = p.out + ((long)o * p.C + c) * T;
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int t = 0; t < T; ++t) dst[t] = acc[t][j];
+            for (int ni = 0; ni < NI; ++ni) {
+                const int c = c0 + (wn * NI + ni) * 32 + l32;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int o = o0 + (wm * MI + mi) * 32 + 8 * (j / 4) + 4 * half + (j % 4);
+                    if (o < p.K && c < p.C) {
+                        float *dst = p.out + ((long)o * p.C + c) * T;
+#pragma unroll
+                        for (int t = 0; t < T; ++t) dst[t] = acc[mi][ni][t][j];
+                    }
+                }
             }
-        }
     } else {
-        // partial sums in fragment order: [slice][tile][wave][tap][register][lane]
-        float *dst = p.out + ((((long)slice * ntiles + tile) * 4 + wave) * T) * 16 * 64 + lane;
+        // partial sums in fragment order: [slice][tile][wave][mi][ni][tap][j/4][lane][j%4]
+        typedef __attribute__((ext_vector_type(4))) float f32x4;
+        f32x4 *dst = (f32x4 *)p.out + (((long)slice * ntiles + tile) * (WM * WN) + wave) * (MI * NI * T * 4 * 64) + lane;
 #pragma unroll
-        for (int t = 0; t < T; ++t)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) dst[(t * 16 + j) * 64] = acc[t][j];
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+#pragma unroll
+                    for (int jq = 0; jq < 4; ++jq) {
+                        const f32x16 &a16 = acc[mi][ni][t];
+                        dst[(((mi * NI + ni) * T + t) * 4 + jq) * 64] =
+                            f32x4{a16[4 * jq], a16[4 * jq + 1], a16[4 * jq + 2], a16[4 * jq + 3]};
+                    }
     }
 }
 
 // Sums the slices' partial tiles in slice order and writes dW in its own layout.
-__global__ void __launch_bounds__(256) dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW, int nslices,
-                                                        int tiles_o, int tiles_c, int T, int K, int C)
+// A block of 256 threads owns 256/SY groups of 4 consecutive partial elements
+// (one 16-byte load per slice and thread); its SY thread rows take every SY-th
+// slice each and are combined through LDS in a fixed order, so the result does
+// not depend on scheduling.
+struct ReduceShape {
+    int nslices, tiles_o, tiles_c, T, K, C, MI, NI, WM, WN;
+};
+template <int SY>
+__global__ void __launch_bounds__(256) dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW, ReduceShape s)
 {
-    const long per_slice = (long)tiles_o * tiles_c * 4 * T * 16 * 64;
-    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= per_slice) return;
-    float s = 0.f;
-    for (int sl = 0; sl < nslices; ++sl) s += part[sl * per_slice + idx];
-    const int lane = idx & 63;
-    long t1 = idx >> 6;
-    const int j = t1 & 15;
-    t1 >>= 4;
-    const int tap = t1 % T;
-    t1 /= T;
-    const int wave = t1 & 3;
-    const int tile = t1 >> 2;
-    const int ot = tile / tiles_c, ct = tile - ot * tiles_c;
-    const int o = ot * 64 + (wave & 1) * 32 + 8 * (j / 4) + 4 * (lane >> 5) + (j % 4);
-    const int c = ct * 64 + (wave >> 1) * 32 + (lane & 31);
-    if (o < K && c < C) dW[((long)o * C + c) * T + tap] = s;
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    constexpr int CX = 256 / SY;
+    __shared__ f32x4 red[SY > 1 ? SY : 1][CX];
+    const int cx = threadIdx.x % CX, sy = threadIdx.x / CX;
+    const long per_tile = (long)s.WM * s.WN * s.MI * s.NI * s.T * 16 * 64;
+    const long per_slice4 = per_tile * s.tiles_o * s.tiles_c / 4;
+    const long col = (long)blockIdx.x * CX + cx; // index of the group of 4 elements
+    if (col >= per_slice4) return;                // (whole blocks only: per_slice4 is a multiple of 256)
+    const f32x4 *src = (const f32x4 *)part + col;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    int sl = sy;
+    for (; sl + 3 * SY < s.nslices; sl += 4 * SY) {
+        const f32x4 a = src[(long)sl * per_slice4], b = src[(long)(sl + SY) * per_slice4];
+        const f32x4 c = src[(long)(sl + 2 * SY) * per_slice4], d = src[(long)(sl + 3 * SY) * per_slice4];
+        sum += a;
+        sum += b;
+        sum += c;
+        sum += d;
+    }
+    for (; sl < s.nslices; sl += SY) sum += src[(long)sl * per_slice4];
+    if (SY > 1) {
+        red[sy][cx] = sum;
+        __syncthreads();
+        if (sy != 0) return;
+#pragma unroll
+        for (int k = 1; k < SY; ++k) sum += red[k][cx];
+    }
+    // col -> [tile][wave][mi][ni][tap][j/4][lane]; the 4 elements are registers 4*(j/4)..+3
+    const int lane = col & 63;
+    long t1 = col >> 6;
+    const int jq = t1 & 3;
+    t1 >>= 2;
+    const int tap = t1 % s.T;
+    t1 /= s.T;
+    const int ni = t1 % s.NI;
+    t1 /= s.NI;
+    const int mi = t1 % s.MI;
+    t1 /= s.MI;
+    const int wave = t1 % (s.WM * s.WN);
+    const int tile = t1 / (s.WM * s.WN);
+    const int wm = wave % s.WM, wn = wave / s.WM;
+    const int ot = tile / s.tiles_c, ct = tile - ot * s.tiles_c;
+    const int c = (ct * s.WN + wn) * s.NI * 32 + ni * 32 + (lane & 31);
+    if (c >= s.C) return;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        // accumulator register j = 4*jq + e holds row 8*(j/4) + 4*(lane/32) + j%4
+        const int o = (ot * s.WM + wm) * s.MI * 32 + mi * 32 + 8 * jq + 4 * (lane >> 5) + e;
+        if (o < s.K) dW[((long)o * s.C + c) * s.T + tap] = sum[e];
+    }
+}
+
+// The same reduction for few slices and large outputs: a block owns one wave's
+// 32 (o) x 32 (c) x taps block, sums it over the slices (slice order), transposes
+// it through LDS and writes whole rows of dW (32*T consecutive floats) instead
+// of single floats.
+template <int T>
+__global__ void __launch_bounds__(256) dw_reduce_tile_kernel(const float *__restrict__ part, float *__restrict__ dW, ReduceShape s)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    __shared__ float red[32][32 * T + 1];
+    const int t = threadIdx.x, lane = t & 63, jq = t >> 6;
+    const long per_tile = (long)s.WM * s.WN * s.MI * s.NI * T * 16 * 64;
+    const long per_slice4 = per_tile * s.tiles_o * s.tiles_c / 4;
+    const f32x4 *src = (const f32x4 *)part + (long)blockIdx.x * (T * 256) + t;
+    f32x4 sum[T];
+#pragma unroll
+    for (int k = 0; k < T; ++k) sum[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int sl = 0; sl < s.nslices; ++sl) {
+        f32x4 v[T];
+#pragma unroll
+        for (int k = 0; k < T; ++k) v[k] = src[(long)sl * per_slice4 + k * 256];
+#pragma unroll
+        for (int k = 0; k < T; ++k) sum[k] += v[k];
+    }
+    // register j = 4*jq + e of lane l holds row 8*jq + 4*(l/32) + e, column l%32
+#pragma unroll
+    for (int k = 0; k < T; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[8 * jq + 4 * (lane >> 5) + e][(lane & 31) * T + k] = sum[k][e];
+    __syncthreads();
+    // block index -> [tile][wave][mi][ni]
+    int b = blockIdx.x;
+    const int ni = b % s.NI;
+    b /= s.NI;
+    const int mi = b % s.MI;
+    b /= s.MI;
+    const int wave = b % (s.WM * s.WN);
+    const int tile = b / (s.WM * s.WN);
+    const int wm = wave % s.WM, wn = wave / s.WM;
+    const int ot = tile / s.tiles_c, ct = tile - ot * s.tiles_c;
+    const int o0 = (ot * s.WM + wm) * s.MI * 32 + mi * 32, c0 = (ct * s.WN + wn) * s.NI * 32 + ni * 32;
+    const int ncols = min(32, s.C - c0) * T; // floats of a row that exist
+    for (int idx = t; idx < 32 * 32 * T; idx += 256) {
+        const int row = idx / (32 * T), col = idx - row * (32 * T);
+        if (o0 + row < s.K && col < ncols) dW[((long)(o0 + row) * s.C + c0) * T + col] = red[row][col];
+    }
 }
 
 uint32_t magic_of(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
@@ -411,18 +642,35 @@ int largest_vec(int extent, int cap)
     return v;
 }
 
-template <int R, int S, int SG, int PAD> hipError_t launch_variant(const DwMfmaParams &p, dim3 grid, hipStream_t st)
+// Kernel table: filter/stride family x workgroup shape.
+struct Variant {
+    int R, SG, MI, NI, WM, WN;
+    hipError_t (*launch)(const DwMfmaParams &, dim3, hipStream_t);
+};
+
+template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN>
+hipError_t launch_variant(const DwMfmaParams &p, dim3 grid, hipStream_t st)
 {
-    auto kern = dw_mfma_kernel<R, S, SG, PAD>;
+    auto kern = dw_mfma_kernel<R, S, SG, PAD, MI, NI, WM, WN>;
     static bool attr_set = false; // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), p.lds_bytes, st, p);
+    hipLaunchKernelGGL(kern, grid, dim3(128 * WM * WN), p.lds_bytes, st, p);
     return hipGetLastError();
 }
+
+const Variant kVariants[] = {
+    {3, 1, 1, 1, 2, 2, launch_variant<3, 3, 1, 1, 1, 1, 2, 2>}, // 3x3: 64 x 64 tile, 144 accumulators per wave
+    {3, 2, 1, 1, 2, 2, launch_variant<3, 3, 2, 1, 1, 1, 2, 2>},
+    {1, 1, 2, 2, 2, 2, launch_variant<1, 1, 1, 0, 2, 2, 2, 2>}, // 1x1: 128 x 128 tile
+    {1, 1, 2, 2, 1, 1, launch_variant<1, 1, 1, 0, 2, 2, 1, 1>}, // 1x1:  64 x 64 tile, one wave
+    {1, 2, 2, 2, 2, 2, launch_variant<1, 1, 2, 0, 2, 2, 2, 2>},
+    {1, 2, 2, 2, 1, 1, launch_variant<1, 1, 2, 0, 2, 2, 1, 1>},
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 } // namespace
 
@@ -436,7 +684,26 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
     const int khl = log2_of(g.kh), kwl = log2_of(g.kw);
     if (khl < 0 || kwl < 0) return false;
     if (g.Q > 256 || g.W > 1024) return false;
+    // buffer loads address with 32-bit byte offsets and use 2^31 as "no load"
+    if ((long)g.N * g.K * g.P * g.Q >= (1L << 30) || (long)g.N * g.C * g.Hp * g.Wp >= (1L << 30)) return false;
     const int T = g.R * g.S;
+
+    // workgroup shape: the large tile unless it would be mostly padding
+    int vi = -1;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.R != g.R || v.SG != g.sh) continue;
+        const int to = 32 * v.MI * v.WM, tc = 32 * v.NI * v.WN;
+        const bool big = to > 64;
+        if (big && (g.K <= to / 2 || g.C <= tc / 2)) continue;
+        vi = i;
+        break;
+    }
+    if (vi < 0) return false;
+    const Variant &var = kVariants[vi];
+    const int NT = 64 * var.WM * var.WN;
+    const int tile_o = 32 * var.MI * var.WM, tile_c = 32 * var.NI * var.WN;
+    const int lds_budget = (NT == 256 ? 156 : NT == 128 ? 78 : 39) * 1024; // whole CU / half / quarter
 
     DwMfmaParams base{};
     base.N = g.N; base.C = g.C; base.K = g.K; base.H = g.H; base.W = g.W; base.P = g.P; base.Q = g.Q;
@@ -445,12 +712,17 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
     base.SEGS = (g.Q + 7) / 8;
     base.Qpad = base.SEGS * 8;
     base.XB = (g.W + 7) / 8;
-    base.ZV = (g.Wp + 3) / 4;
-    base.XW = 8 * ((max(g.W, base.ZV * 4 * g.kw) + 7) / 8);
+    base.ZV = (g.Wp + 7) / 8;
+    const int NPH = g.S == 1 ? 1 : g.sh;  // xhat column phases kept per row
+    // width of one phase of an xhat row in LDS: the padded output row, or what the
+    // staging of whole 8-value items writes if that is more
+    const int f_log2 = kwl - (g.sh == 2 ? 1 : 0);
+    base.PW = max(base.Qpad, f_log2 >= 0 ? (8 * base.ZV) << f_log2 : 4 * base.ZV);
+    base.XW = NPH * base.PW;              // one xhat row in LDS: all phases
+    base.tile_o = tile_o; base.tile_c = tile_c;
 
     // Fills the chunk-dependent fields; false when the chunk does not fit the
-    // per-thread copy registers or the LDS budget of two workgroups per CU
-    // (two buffers each).
+    // per-thread copy registers or the LDS budget (two buffers).
     auto shape = [&](int nbi, int pr, DwMfmaParams &q) {
         q = base;
         q.NBI = nbi; q.PR = pr;
@@ -467,16 +739,20 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
         q.NZ = nz;
         q.rowitems = q.LRpad * q.SEGS;
         q.citems = nbi * nz * q.ZV;
-        if (q.rowitems > 4 * kMaxDy || q.citems > 4 * kMaxZ) return false;
-        auto pow2_at_least = [](int x) { int v = 4, l = 2; while (v < x) { v *= 2; ++l; } return l; };
-        q.ldy_log2 = pow2_at_least(q.rowitems); q.LDY = 1 << q.ldy_log2; q.dy_passes = q.LDY / 4;
-        q.lpc_log2 = pow2_at_least(q.citems);   q.LPC = 1 << q.lpc_log2; q.z_passes = q.LPC / 4;
+        auto pow2_at_least = [](int x) { int l = 2; while ((1 << l) < x) ++l; return l; };
+        q.ldy_log2 = pow2_at_least(q.rowitems); q.LDY = 1 << q.ldy_log2;
+        q.lpc_log2 = pow2_at_least(q.citems);   q.LPC = 1 << q.lpc_log2;
+        if (q.LDY > NT || q.LPC > NT) return false;
+        q.dy_passes = (tile_o * q.LDY + NT - 1) / NT;
+        q.z_passes = (tile_c * q.LPC + NT - 1) / NT;
+        if (q.dy_passes > kMaxDy || q.z_passes > kMaxZ) return false;
+        if ((tile_o * q.LDY) % NT || (tile_c * q.LPC) % NT) return false; // passes cover the tile exactly
         // strides: an odd number of 16-byte units so that the 32 lanes of a half
         // wave (one output channel / input channel each) read distinct LDS banks
-        q.dy_ostride = 8 * (q.rowitems | 1);
-        q.x_cstride = 8 * ((nbi * nz * (q.XW / 8)) | 1);
-        q.lds_bytes = (q.XW + 2 * (64 * q.dy_ostride + 64 * q.x_cstride)) * 2;
-        return q.lds_bytes <= 78 * 1024;
+        q.dy_ostride = 8 * ((q.rowitems + 1) | 1); // + one block: the dY window looks one block past a row
+        q.x_cstride = 8 * (((nbi * nz + 1) * (q.XW / 8)) | 1); // + the zero slot
+        q.lds_bytes = (q.XW + 2 * (q.LRpad * 8 + tile_o * q.dy_ostride + tile_c * q.x_cstride)) * 2;
+        return q.lds_bytes <= lds_budget;
     };
     // Candidates: part of one image (nbi = 1, pr <= P) or several whole images.
     // Cost = MFMA steps spent per useful pixel row, then prefer longer chunks.
@@ -488,7 +764,7 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
         const double steps = (double)q.RB * (q.LRpad / 2) * q.SEGS;      // per group of nbi images
         const double useful = (double)nbi * g.P * g.Q / 16.0;
         const double per_chunk = (q.LRpad / 2) * q.SEGS;
-        const double cost = steps / useful * (1.0 + 2.5 / per_chunk);     // barrier + epilogue share
+        const double cost = steps / useful * (1.0 + 1.5 / per_chunk);     // barrier + refill share
         if (cost < best_cost) { best_cost = cost; best = q; }
     };
     for (int pr = 1; pr <= g.P; ++pr) consider(1, pr);
@@ -497,30 +773,31 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
 
     DwMfmaParams &p = plan->p;
     p = best;
-    p.m_rowitems = magic_of(p.rowitems);
     p.m_segs = magic_of(p.SEGS);
     p.m_pr = magic_of(p.PR);
-    p.m_citems = magic_of(p.citems);
     p.m_zv = magic_of(p.ZV);
     p.m_nz = magic_of(p.NZ);
     // widest aligned vector for the global reads (tensor bases are 16-byte aligned)
-    p.dy_vec = largest_vec(g.Q, 8);
-    p.z_vec = largest_vec(g.Wp, 4);
+    p.dy_vec = largest_vec(g.Q, 8);   // (informational: every read is a 16-byte load)
+    p.z_vec = largest_vec(g.Wp, 8);
 
-    p.tiles_o = (g.K + 63) / 64;
-    p.tiles_c = (g.C + 63) / 64;
+    p.tiles_o = (g.K + tile_o - 1) / tile_o;
+    p.tiles_c = (g.C + tile_c - 1) / tile_c;
     const int ntiles = p.tiles_o * p.tiles_c;
     p.nchunks = ((g.N + p.NBI - 1) / p.NBI) * p.RB;
-    // enough workgroups for two per CU on 256 CUs, each with at least two chunks
-    int want = max(1, (512 + ntiles - 1) / ntiles);
+    // one workgroup per 256 threads of the 256 CUs, each with at least two chunks
+    const int wg_target = 256 * (256 / NT);
+    int want = max(1, wg_target / ntiles);
     want = min(want, max(1, p.nchunks / 2));
     p.chunks_per_slice = (p.nchunks + want - 1) / want;
     p.nslices = (p.nchunks + p.chunks_per_slice - 1) / p.chunks_per_slice;
     p.total_wg = p.nslices * ntiles;
     p.direct = p.nslices == 1;
     plan->grid = ((p.total_wg + 7) / 8) * 8;
-    plan->partial_bytes = p.direct ? 0 : (size_t)p.nslices * ntiles * 4 * T * 16 * 64 * sizeof(float);
-    plan->variant = (f3 ? 0 : 2) + (g.sh == 2 ? 1 : 0);
+    plan->threads = NT;
+    plan->tile_elems = (long)tile_o * tile_c * T;
+    plan->partial_bytes = p.direct ? 0 : (size_t)p.nslices * ntiles * plan->tile_elems * sizeof(float);
+    plan->variant = vi;
     return true;
 }
 
@@ -530,19 +807,26 @@ hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY,
     p.Z = (const bf16_t *)Z;
     p.dY = (const bf16_t *)dY;
     p.out = p.direct ? dW : (float *)ws;
-    dim3 grid(plan.grid);
-    hipError_t e;
-    switch (plan.variant) {
-    case 0: e = launch_variant<3, 3, 1, 1>(p, grid, st); break;
-    case 1: e = launch_variant<3, 3, 2, 1>(p, grid, st); break;
-    case 2: e = launch_variant<1, 1, 1, 0>(p, grid, st); break;
-    default: e = launch_variant<1, 1, 2, 0>(p, grid, st); break;
-    }
+    if (const char *e = getenv("CAC_DW_DEBUG")) p.dbg = atoi(e);
+    const Variant &var = kVariants[plan.variant];
+    hipError_t e = var.launch(p, dim3(plan.grid), st);
     if (e != hipSuccess || p.direct) return e;
-    const int T = plan.variant < 2 ? 9 : 1;
-    const long per_slice = (long)p.tiles_o * p.tiles_c * 4 * T * 16 * 64;
-    hipLaunchKernelGGL(dw_reduce_kernel, dim3((unsigned)((per_slice + 255) / 256)), dim3(256), 0, st,
-                       (const float *)ws, dW, p.nslices, p.tiles_o, p.tiles_c, T, p.K, p.C);
+    ReduceShape rs{p.nslices, p.tiles_o, p.tiles_c, var.R * var.R, p.K, p.C, var.MI, var.NI, var.WM, var.WN};
+    const long per_slice = plan.tile_elems * p.tiles_o * p.tiles_c;
+    // thread rows over the slices: enough of them to keep a few hundred thousand loads in flight
+    const long cols = per_slice / 4;
+    if (p.nslices <= 8 && cols >= (1 << 16)) {
+        const unsigned blocks = (unsigned)(per_slice / (1024 * rs.T));
+        if (rs.T == 9)
+            hipLaunchKernelGGL(dw_reduce_tile_kernel<9>, dim3(blocks), dim3(256), 0, st, (const float *)ws, dW, rs);
+        else
+            hipLaunchKernelGGL(dw_reduce_tile_kernel<1>, dim3(blocks), dim3(256), 0, st, (const float *)ws, dW, rs);
+    } else if (p.nslices <= 8 || cols >= (1 << 18))
+        hipLaunchKernelGGL(dw_reduce_kernel<1>, dim3((unsigned)(cols / 256)), dim3(256), 0, st, (const float *)ws, dW, rs);
+    else if (p.nslices <= 32 || cols >= (1 << 16))
+        hipLaunchKernelGGL(dw_reduce_kernel<4>, dim3((unsigned)(cols / 64)), dim3(256), 0, st, (const float *)ws, dW, rs);
+    else
+        hipLaunchKernelGGL(dw_reduce_kernel<16>, dim3((unsigned)(cols / 16)), dim3(256), 0, st, (const float *)ws, dW, rs);
     return hipGetLastError();
 }
 

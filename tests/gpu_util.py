@@ -14,19 +14,11 @@ CANARY = 0xA5
 
 
 def upload(a: np.ndarray, dtype: str) -> torch.Tensor:
-    """float32 host array (already rounded to `dtype`) -> device tensor of that dtype."""
-    if dtype == synth.F32:
-        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
-    bits = synth.bf16_bits(a).view(np.int16)
-    return torch.from_numpy(bits).to(DEV).view(torch.bfloat16)
+    return B.to_device(a, dtype, DEV)
 
 
 def download(t: torch.Tensor) -> np.ndarray:
-    """device tensor -> float64 host array (bfloat16 widened exactly)."""
-    if t.dtype == torch.bfloat16:
-        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-        return synth.bf16_from_bits(bits).astype(np.float64)
-    return t.cpu().numpy().astype(np.float64)
+    return B.to_host(t)
 
 
 class Guarded:
