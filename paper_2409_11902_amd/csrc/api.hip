@@ -108,6 +108,8 @@ static int check_ws(const Geom &g, int dtype, int op, const void *ws, size_t ws_
 
 static hipError_t do_compress(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st)
 {
+    hipError_t e = hipSuccess;
+    if (launch_compress_fast(g, dtype, X, Z, st, &e)) return e;
     return launch_compress_generic(g, dtype, X, Z, st);
 }
 

@@ -43,6 +43,8 @@ template <> struct Elem<bf16_t> {
 
 // ---- launchers implemented in the .hip files.  All enqueue on `st` and return the
 // launch status; operand shapes have been validated by the caller (api.hip).
+// compress.hip: true when the fast kernel covers the geometry and was launched (status in *err)
+bool launch_compress_fast(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st, hipError_t *err);
 hipError_t launch_compress_generic(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st);
 hipError_t launch_fwd_generic(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y,
                               hipStream_t st);

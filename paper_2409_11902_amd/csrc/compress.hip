@@ -1,0 +1,171 @@
+// Activation compression: Z = average pooling of X over non-overlapping,
+// origin-aligned kh x kw tiles (compression section; the compression figure
+// shows the tiling).  Bandwidth-bound: every element of X is read once with
+// 16-byte loads, every element of Z written once; no LDS.
+//
+// A thread owns one "chunk": 16 bytes of kh consecutive input rows (8 bfloat16
+// or 4 float columns) and the 16/(kw*elem) pooled values below them.  Chunks of
+// a row are handed to consecutive threads, so a wave reads whole rows.
+// Ragged edges follow the ceil/valid rule: a tile that sticks out is averaged
+// over the elements it really has.
+#include "common.h"
+
+namespace cac {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kNoLoad = 0x80000000u;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
+// EPC consecutive elements starting at element e (any alignment the type
+// allows) as floats; elements past the tensor read as zero.
+template <typename T, int EPC> struct Chunk;
+template <int EPC> struct Chunk<bf16_t, EPC> {
+    static_assert(EPC == 8 || EPC == 4, "");
+    // odd: rows can start on odd elements (odd W); only then the extra dword is fetched
+    static __device__ __forceinline__ void load(rsrc_t rs, uint32_t e, bool live, bool odd, float (&out)[EPC])
+    {
+        // dword-aligned address at or below the element; an odd start is shifted out afterwards
+        const uint32_t byte = live ? (e & ~1u) * 2u : kNoLoad;
+        uint32_t d[EPC / 2 + 1];
+        d[EPC / 2] = 0;
+        if constexpr (EPC == 8) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, byte, 0, 0);
+            d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
+            if (odd) d[4] = __builtin_amdgcn_raw_buffer_load_b32(rs, byte == kNoLoad ? kNoLoad : byte + 16, 0, 0);
+        } else {
+            typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, byte, 0, 0);
+            d[0] = v[0]; d[1] = v[1];
+            if (odd) d[2] = __builtin_amdgcn_raw_buffer_load_b32(rs, byte == kNoLoad ? kNoLoad : byte + 8, 0, 0);
+        }
+        const uint32_t sh = (e & 1u) * 16u;
+#pragma unroll
+        for (int j = 0; j < EPC / 2; ++j) {
+            const uint32_t w = __builtin_amdgcn_alignbit(d[j + 1], d[j], sh);
+            out[2 * j] = __uint_as_float(w << 16);
+            out[2 * j + 1] = __uint_as_float(w & 0xffff0000u);
+        }
+    }
+};
+template <> struct Chunk<float, 4> {
+    static __device__ __forceinline__ void load(rsrc_t rs, uint32_t e, bool live, bool, float (&out)[4])
+    {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, live ? e * 4u : kNoLoad, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = __uint_as_float(v[j]);
+    }
+};
+
+// floor(x / d) for x < 2^31 and d < 2^16, given inv = 1.0 / d: the quotient's
+// fractional part is a multiple of 1/d >= 2^-16, so adding 2^-18 before
+// truncating absorbs the rounding of x * inv without ever reaching the next integer.
+__device__ __forceinline__ uint32_t udiv(uint32_t x, double inv) { return (uint32_t)((double)x * inv + 0x1p-18); }
+
+template <typename T, int EPC, int KH, int KW>
+__global__ void __launch_bounds__(256) compress_kernel(Geom g, const T *__restrict__ X, T *__restrict__ Z, int cpr,
+                                                       uint32_t total, double inv_cpr, double inv_hp)
+{
+    constexpr int OPC = EPC / KW; // pooled values per chunk
+    static_assert(OPC >= 1, "");
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    // idx -> (plane, pooled row i, chunk c), chunk fastest
+    const uint32_t rowi = udiv(idx, inv_cpr);
+    const uint32_t c = idx - rowi * cpr;
+    const uint32_t plane = udiv(rowi, inv_hp);
+    const uint32_t i = rowi - plane * g.Hp;
+
+    const rsrc_t rs = make_rsrc(X, (uint32_t)g.N * g.C * g.H * g.W * (uint32_t)sizeof(T));
+    const int h0 = i * KH;
+    const int rows = min(KH, g.H - h0);
+    float v[KH][EPC];
+#pragma unroll
+    for (int a = 0; a < KH; ++a)
+        Chunk<T, EPC>::load(rs, (plane * g.H + h0 + a) * g.W + c * EPC, a < rows, g.W & 1, v[a]);
+
+    const int w0 = c * EPC;       // first input column of the chunk
+    const int j0 = c * OPC;       // first pooled column
+    T *zrow = Z + ((long)plane * g.Hp + i) * g.Wp;
+    const float inv_full = 1.0f / (float)(rows * KW); // exact for the power-of-two counts of whole tiles
+    float res[OPC];
+#pragma unroll
+    for (int o = 0; o < OPC; ++o) {
+        const int cols = min(KW, g.W - (w0 + o * KW)); // < 1 for pooled columns that do not exist
+        float sum = 0.f;
+#pragma unroll
+        for (int a = 0; a < KH; ++a)
+#pragma unroll
+            for (int b = 0; b < KW; ++b)
+                if (a < rows && b < cols) sum += v[a][o * KW + b];
+        res[o] = cols == KW ? sum * inv_full : sum / (float)(rows * max(cols, 1));
+    }
+    if (g.Wp % OPC == 0) {
+        // whole chunks only, and the row of Z starts on a multiple of OPC elements: one store
+        if constexpr (sizeof(T) == 4) {
+            typedef __attribute__((ext_vector_type(OPC))) float fvec;
+            fvec out;
+#pragma unroll
+            for (int o = 0; o < OPC; ++o) out[o] = res[o];
+            *(fvec *)(zrow + j0) = out;
+        } else if constexpr (OPC >= 2) {
+            typedef __attribute__((ext_vector_type(OPC / 2))) uint32_t uvec;
+            uvec out;
+#pragma unroll
+            for (int o = 0; o < OPC / 2; ++o)
+                out[o] = (uint32_t)f32_to_bf16(res[2 * o]) | ((uint32_t)f32_to_bf16(res[2 * o + 1]) << 16);
+            *(uvec *)(zrow + j0) = out;
+        } else {
+            Elem<T>::store(zrow + j0, res[0]);
+        }
+    } else {
+#pragma unroll
+        for (int o = 0; o < OPC; ++o)
+            if (j0 + o < g.Wp) Elem<T>::store(zrow + j0 + o, res[o]);
+    }
+}
+
+template <typename T, int EPC> bool launch_epc(const Geom &g, const void *X, void *Z, hipStream_t st)
+{
+    const int cpr = (g.W + EPC - 1) / EPC;
+    const long total = (long)g.N * g.C * g.Hp * cpr;
+    if (total >= (1L << 31) || cpr >= (1 << 16) || g.Hp >= (1 << 16)) return false; // udiv's range
+    const dim3 grid((unsigned)((total + 255) / 256));
+#define CAC_LAUNCH(KH, KW)                                                                                     \
+    hipLaunchKernelGGL((compress_kernel<T, EPC, KH, KW>), grid, dim3(256), 0, st, g, (const T *)X, (T *)Z, cpr, \
+                       (uint32_t)total, 1.0 / cpr, 1.0 / g.Hp)
+    if (g.kh == 2 && g.kw == 2) CAC_LAUNCH(2, 2);
+    else if (g.kh == 4 && g.kw == 4) CAC_LAUNCH(4, 4);
+    else if (g.kh == 1 && g.kw == 1) CAC_LAUNCH(1, 1);
+    else if (g.kh == 2 && g.kw == 4) CAC_LAUNCH(2, 4);
+    else if (g.kh == 4 && g.kw == 2) CAC_LAUNCH(4, 2);
+    else return false;
+#undef CAC_LAUNCH
+    return true;
+}
+
+} // namespace
+
+// True when the fast kernel covers the geometry (and has been launched).
+bool launch_compress_fast(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st, hipError_t *err)
+{
+    if ((long)g.N * g.C * g.H * g.W * 4 >= (1L << 31)) return false; // 32-bit buffer offsets
+    bool ok;
+    if (dtype == CAC_F32) {
+        if (g.kw > 4) return false;
+        ok = launch_epc<float, 4>(g, X, Z, st);
+    } else {
+        // narrow maps: 8-byte chunks so that a chunk does not span more than one row's worth
+        ok = g.W >= 8 ? launch_epc<bf16_t, 8>(g, X, Z, st) : (g.kw <= 4 ? launch_epc<bf16_t, 4>(g, X, Z, st) : false);
+    }
+    if (ok) *err = hipGetLastError();
+    return ok;
+}
+
+} // namespace cac
