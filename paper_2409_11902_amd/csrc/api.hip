@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include "common.h"
+#include "conv_mfma.h"
 #include "dw_mfma.h"
 
 namespace cac {
@@ -92,6 +93,9 @@ static size_t workspace_bytes(const Geom &g, int dtype, int op)
         DwMfmaPlan plan;
         if (dw_mfma_plan(g, dtype, &plan)) return plan.partial_bytes; // partial sums of the pixel slices
     }
+    // channels-last copy of the input and the repacked filter
+    if (op == CAC_OP_FWD_AND_COMPRESS) return conv_mfma_workspace(g, dtype, false);
+    if (op == CAC_OP_BWD_DATA) return conv_mfma_workspace(g, dtype, true);
     return 0;
 }
 
@@ -191,8 +195,10 @@ int conv_fwd_and_compress(const cac_desc *d, const void *X, const void *W, const
     if (d->has_bias && (rc = check_ptr(b, "b"))) return rc;
     if ((rc = check_ws(g, d->dtype, CAC_OP_FWD_AND_COMPRESS, ws, ws_bytes, nullptr))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = launched(launch_fwd_generic(g, d->dtype, X, W, d->has_bias ? b : nullptr, Y, st), "forward convolution")))
-        return rc;
+    hipError_t e = hipSuccess;
+    if (!launch_fwd_mfma(g, d->dtype, X, W, d->has_bias ? b : nullptr, Y, ws, st, &e))
+        e = launch_fwd_generic(g, d->dtype, X, W, d->has_bias ? b : nullptr, Y, st);
+    if ((rc = launched(e, "forward convolution"))) return rc;
     return launched(do_compress(g, d->dtype, X, Z, st), "compress");
 }
 
@@ -227,7 +233,10 @@ int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX, vo
     if (rc) return rc;
     if ((rc = check_ptr(W, "W")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dX, "dX"))) return rc;
     if ((rc = check_ws(g, d->dtype, CAC_OP_BWD_DATA, ws, ws_bytes, nullptr))) return rc;
-    return launched(launch_dx_generic(g, d->dtype, W, dY, dX, (hipStream_t)stream), "data gradient");
+    hipError_t e = hipSuccess;
+    if (!launch_dx_mfma(g, d->dtype, W, dY, dX, ws, (hipStream_t)stream, &e))
+        e = launch_dx_generic(g, d->dtype, W, dY, dX, (hipStream_t)stream);
+    return launched(e, "data gradient");
 }
 
 int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream)

@@ -1,0 +1,28 @@
+// Forward convolution / data gradient as an MFMA gather GEMM (see conv_mfma.hip).
+#pragma once
+#include "common.h"
+
+namespace cac {
+
+struct GatherParams {
+    const bf16_t *in;   // [N][Hin][Win][KCp], channels last
+    const bf16_t *wt;   // [ntaps_total][Mp][KCp]
+    const bf16_t *bias; // [M] or null
+    bf16_t *out;        // [N][M][Hout][Wout]
+    int N, M, Mp, KCp;
+    int Hin, Win, Hout, Wout;
+    int Hc, Wc;         // grid of output pixels of this launch: (h, w) = (i*os + a0, j*os + b0)
+    int os, a0, b0, is; // input pixel of tap t: (i*is + dh[t], j*is + dw[t])
+    int ntaps, ntaps_total;
+    int dh[9], dw[9], wtap[9];
+    int dhmin, dwmin;
+    int PH, PWd;        // input patch staged per workgroup (rows, columns)
+};
+
+size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad);
+bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *ws,
+                     hipStream_t st, hipError_t *err);
+bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,
+                    hipError_t *err);
+
+} // namespace cac

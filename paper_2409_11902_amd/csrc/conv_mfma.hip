@@ -1,0 +1,361 @@
+// Forward convolution and data gradient (forward / data-gradient formulas of the
+// compression figure; neither depends on the compressed activation) as one MFMA
+// implicit GEMM over channels-last copies of their inputs.
+//
+// Both are the same "gather" sum
+//   out[n, m, h, w] = bias[m] + sum_t sum_kc Wt[t][m][kc] * in[n, i*is + dh_t, j*is + dw_t, kc]
+// over a list of taps t, for the output pixels (h, w) = (i*os + a0, j*os + b0):
+//   forward:            in = X,  m = o, kc = c, os = 1, is = stride, (dh, dw) = (r - pad, s - pad)
+//   data gradient, s=1: in = dY, m = c, kc = o, os = 1, is = 1,      (dh, dw) = (pad - r, pad - s)
+//   data gradient, s=2: one launch per output parity class (a0, b0) with the
+//                       taps whose (a0 + pad - r) and (b0 + pad - s) are even.
+// The reduction index kc must be contiguous per pixel for the MFMA operand
+// layout, hence a channels-last repack of the input (workspace) and a
+// [tap][m][kc] repack of the filter, both padded with zeros to multiples of 16.
+//
+// Workgroup: 4 waves as WM x WN; a wave owns 64 (m) x 32*NI (pixels).  The input
+// patch of the pixel tile (with its halo, KC channels at a time) is staged in
+// LDS once and serves every tap; filter fragments come straight from global
+// memory (small, cache resident), fetched one step ahead.
+#include "common.h"
+#include "conv_mfma.h"
+
+namespace cac {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kNoLoad = 0x80000000u;
+constexpr int KC = 32;       // channels staged per pass
+constexpr int KCS = KC + 8;  // LDS elements per patch pixel: 80 bytes, an odd number of 16-byte units
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
+// ---- repacks ---------------------------------------------------------------------
+
+// in [N][C][HW] -> out [N][HW][Cp], zeros for c >= C.  One block: 64 pixels x 64 channels.
+__global__ void __launch_bounds__(256) nchw_to_nhwc_kernel(const bf16_t *__restrict__ in, bf16_t *__restrict__ out, int C,
+                                                           int HW, int Cp)
+{
+    __shared__ bf16_t tile[64][66];
+    const int n = blockIdx.z, c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int k = ty; k < 64; k += 4) {
+        const int c = c0 + k, px = p0 + tx;
+        tile[k][tx] = (c < C && px < HW) ? in[((long)n * C + c) * HW + px] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int k = ty; k < 64; k += 4) {
+        const int px = p0 + k, c = c0 + tx;
+        if (px < HW && c < Cp) out[((long)n * HW + px) * Cp + c] = tile[tx][k];
+    }
+}
+
+// W [O][C][R][S] -> Wt [R*S][Mp][KCp]; forward: m = o, kc = c; data gradient: m = c, kc = o.
+__global__ void __launch_bounds__(256) filter_repack_kernel(const bf16_t *__restrict__ W, bf16_t *__restrict__ Wt, int O, int C,
+                                                            int RS, int Mp, int KCp, int transpose)
+{
+    const long total = (long)RS * Mp * KCp;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int kc = idx % KCp;
+    const long t1 = idx / KCp;
+    const int m = t1 % Mp, tap = t1 / Mp;
+    const int o = transpose ? kc : m, c = transpose ? m : kc;
+    Wt[idx] = (o < O && c < C) ? W[((long)o * C + c) * RS + tap] : (bf16_t)0;
+}
+
+__global__ void __launch_bounds__(256) zero_fill_kernel(u32x4 *dst, long n16)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = u32x4{0, 0, 0, 0};
+}
+
+// ---- the gather GEMM ----------------------------------------------------------------
+
+template <int NI, int WM, int WN>
+__global__ void __launch_bounds__(256) conv_gather_kernel(GatherParams p)
+{
+    constexpr int MI = 2;
+    constexpr int PT = WN * NI * 32; // pixels per workgroup
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t *patch = (bf16_t *)smem;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM, half = lane >> 5, l32 = lane & 31;
+    const int tiles_per_img = (p.Hc * p.Wc + PT - 1) / PT;
+    const int n = blockIdx.x / tiles_per_img, tile = blockIdx.x - n * tiles_per_img;
+    const int pix0 = tile * PT;                    // first class-grid pixel of the tile
+    const int i0 = pix0 / p.Wc;                    // its row
+    const int m0 = (blockIdx.y * WM + wm) * 64;    // this wave's first output channel
+
+    // input patch: rows i0*is + dhmin ..., all columns dwmin ... (Wc-1)*is + dwmax
+    const int hin0 = i0 * p.is + p.dhmin, win0 = p.dwmin;
+    const int patch_px = p.PH * p.PWd;
+
+    // this lane's pixels: LDS byte offset of their tap-(dhmin,dwmin) input pixel; class-grid coordinates
+    uint32_t pbase[NI];
+    int pi[NI], pj[NI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int px = pix0 + (wn * NI + ni) * 32 + l32;
+        const bool ok = px < p.Hc * p.Wc;
+        const int i = px / p.Wc, j = px - i * p.Wc;
+        pi[ni] = ok ? i : -1;
+        pj[ni] = j;
+        pbase[ni] = ok ? (uint32_t)(((i - i0) * p.is * p.PWd + j * p.is) * KCS * 2) : 0u;
+    }
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.f;
+
+    const rsrc_t rs_in = make_rsrc(p.in, (uint32_t)p.N * p.Hin * p.Win * p.KCp * 2u);
+    const rsrc_t rs_w = make_rsrc(p.wt, (uint32_t)p.ntaps_total * p.Mp * p.KCp * 2u);
+    const bool wave_live = m0 < p.Mp; // waves past the (padded) output channels only help staging
+
+    // filter fragment of (tap t, channel block kk of 16) for output channel block mi
+    auto wfrag = [&](int t, int kc0, int mi) {
+        const uint32_t e = ((uint32_t)(p.wtap[t] * p.Mp + m0 + mi * 32 + l32) * p.KCp + kc0 + 8 * half) * 2u;
+        return __builtin_amdgcn_raw_buffer_load_b128(rs_w, wave_live ? e : kNoLoad, 0, 0);
+    };
+
+    for (int kcb = 0; kcb < p.KCp; kcb += KC) {
+        // ---- stage the patch: KC channels of every patch pixel, zeros outside the image
+        __syncthreads();
+        for (int it = tid; it < patch_px * (KC / 8); it += 256) {
+            const int pp = it / (KC / 8), v = it - pp * (KC / 8);
+            const int pr = pp / p.PWd, pc = pp - pr * p.PWd;
+            const int hin = hin0 + pr, win = win0 + pc;
+            const bool ok = hin >= 0 && hin < p.Hin && win >= 0 && win < p.Win && kcb + v * 8 < p.KCp;
+            const uint32_t e = (((uint32_t)(n * p.Hin + hin) * p.Win + win) * p.KCp + kcb + v * 8) * 2u;
+            *(u32x4 *)(patch + pp * KCS + v * 8) = __builtin_amdgcn_raw_buffer_load_b128(rs_in, ok ? e : kNoLoad, 0, 0);
+        }
+        __syncthreads();
+        if (!wave_live) continue;
+        // ---- taps x 16-channel blocks, filter fragments one step ahead
+        const int nsteps = p.ntaps * (KC / 16);
+        u32x4 wcur[MI], wnxt[MI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) wcur[mi] = wfrag(0, kcb, mi);
+        for (int st = 0; st < nsteps; ++st) {
+            const int t = st / (KC / 16), kk = st - t * (KC / 16);
+            const int st1 = min(st + 1, nsteps - 1), t1 = st1 / (KC / 16), kk1 = st1 - t1 * (KC / 16);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) wnxt[mi] = wfrag(t1, kcb + kk1 * 16, mi);
+            const uint32_t toff = (uint32_t)(((p.dh[t] - p.dhmin) * p.PWd + (p.dw[t] - p.dwmin)) * KCS + kk * 16 + 8 * half) * 2u;
+            u32x4 b[NI];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) b[ni] = *(const u32x4 *)(smem + pbase[ni] + toff);
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    union { u32x4 u; bf16x8 v; } af, bf;
+                    af.u = wcur[mi];
+                    bf.u = b[ni];
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[mi][ni], 0, 0, 0);
+                }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) wcur[mi] = wnxt[mi];
+        }
+    }
+    if (!wave_live) return;
+
+    // ---- epilogue: bias, bfloat16, NCHW.  Register j of lane l: row 8*(j/4) + 4*(l/32) + j%4, column l%32.
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int m = m0 + mi * 32 + 8 * (j / 4) + 4 * half + (j % 4);
+            if (m >= p.M) continue;
+            const float bias = p.bias ? bf16_to_f32(p.bias[m]) : 0.f;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                if (pi[ni] < 0) continue;
+                const int h = pi[ni] * p.os + p.a0, w = pj[ni] * p.os + p.b0;
+                p.out[(((long)n * p.M + m) * p.Hout + h) * p.Wout + w] = f32_to_bf16(acc[mi][ni][j] + bias);
+            }
+        }
+}
+
+template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p, hipStream_t st)
+{
+    auto kern = conv_gather_kernel<NI, WM, WN>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    constexpr int PT = WN * NI * 32;
+    const int tiles_per_img = (p.Hc * p.Wc + PT - 1) / PT;
+    dim3 grid(tiles_per_img * p.N, (p.Mp / 64 + WM - 1) / WM);
+    hipLaunchKernelGGL(kern, grid, dim3(256), (size_t)p.PH * p.PWd * KCS * 2, st, p);
+    return hipGetLastError();
+}
+
+int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Chooses the workgroup shape and fills the patch extents; false if no shape fits LDS.
+bool shape_gather(GatherParams &p, int *variant)
+{
+    p.dhmin = p.dwmin = 1 << 30;
+    int dhmax = -(1 << 30), dwmax = -(1 << 30);
+    for (int t = 0; t < p.ntaps; ++t) {
+        p.dhmin = min(p.dhmin, p.dh[t]); dhmax = max(dhmax, p.dh[t]);
+        p.dwmin = min(p.dwmin, p.dw[t]); dwmax = max(dwmax, p.dw[t]);
+    }
+    p.PWd = (p.Wc - 1) * p.is + (dwmax - p.dwmin) + 1;
+    const int wm = p.Mp <= 64 ? 1 : p.Mp <= 128 ? 2 : 4, wn = 4 / wm;
+    const int px = p.Hc * p.Wc;
+    // candidates (NI), largest pixel tile first; small maps take a smaller one
+    for (int ni : {4, 2, 1}) {
+        const int pt = wn * ni * 32;
+        if (ni > 1 && px <= pt / 2) continue;
+        const int rows = min(p.Hc, (pt + p.Wc - 2) / p.Wc + 1); // class-grid rows a tile can touch
+        p.PH = (rows - 1) * p.is + (dhmax - p.dhmin) + 1;
+        if ((long)p.PH * p.PWd * KCS * 2 > 150 * 1024) continue;
+        *variant = (ni == 4 ? 0 : ni == 2 ? 3 : 6) + (wm == 1 ? 0 : wm == 2 ? 1 : 2);
+        return true;
+    }
+    return false;
+}
+
+hipError_t run_gather(const GatherParams &p, int variant, hipStream_t st)
+{
+    switch (variant) {
+    case 0: return launch_gather<4, 1, 4>(p, st);
+    case 1: return launch_gather<4, 2, 2>(p, st);
+    case 2: return launch_gather<4, 4, 1>(p, st);
+    case 3: return launch_gather<2, 1, 4>(p, st);
+    case 4: return launch_gather<2, 2, 2>(p, st);
+    case 5: return launch_gather<2, 4, 1>(p, st);
+    case 6: return launch_gather<1, 1, 4>(p, st);
+    case 7: return launch_gather<1, 2, 2>(p, st);
+    default: return launch_gather<1, 4, 1>(p, st);
+    }
+}
+
+bool supported(const Geom &g, int dtype)
+{
+    if (dtype != CAC_BF16) return false;
+    if (g.R * g.S > 9) return false;
+    if (g.sh != g.sw || (g.sh != 1 && g.sh != 2)) return false;
+    // 32-bit byte offsets with 2^31 reserved for "no load"
+    const long lim = 1L << 30;
+    if ((long)g.N * g.H * g.W * round_up(g.C, 16) >= lim || (long)g.N * g.P * g.Q * round_up(g.K, 16) >= lim) return false;
+    return true;
+}
+
+} // namespace
+
+size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad)
+{
+    if (!supported(g, dtype)) return 0;
+    const int RS = g.R * g.S;
+    if (!data_grad) {
+        const size_t in = (size_t)g.N * g.H * g.W * round_up(g.C, 16) * 2;
+        const size_t wt = (size_t)RS * round_up(g.K, 64) * round_up(g.C, 16) * 2;
+        return (in + 255) / 256 * 256 + wt;
+    }
+    const size_t in = (size_t)g.N * g.P * g.Q * round_up(g.K, 16) * 2;
+    const size_t wt = (size_t)RS * round_up(g.C, 64) * round_up(g.K, 16) * 2;
+    return (in + 255) / 256 * 256 + wt;
+}
+
+// Forward: Y = X * W + b.  False when the geometry is not covered.
+bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *ws,
+                     hipStream_t st, hipError_t *err)
+{
+    if (!supported(g, dtype)) return false;
+    GatherParams p{};
+    p.N = g.N; p.M = g.K; p.Mp = round_up(g.K, 64); p.KCp = round_up(g.C, 16);
+    p.Hin = g.H; p.Win = g.W; p.Hout = g.P; p.Wout = g.Q; p.Hc = g.P; p.Wc = g.Q;
+    p.os = 1; p.a0 = p.b0 = 0; p.is = g.sh;
+    p.ntaps = p.ntaps_total = g.R * g.S;
+    for (int r = 0; r < g.R; ++r)
+        for (int s = 0; s < g.S; ++s) {
+            const int t = r * g.S + s;
+            p.dh[t] = r - g.ph; p.dw[t] = s - g.pw; p.wtap[t] = t;
+        }
+    int variant;
+    if (!shape_gather(p, &variant)) return false;
+    const size_t in_bytes = ((size_t)g.N * g.H * g.W * p.KCp * 2 + 255) / 256 * 256;
+    bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + in_bytes);
+    const int HW = g.H * g.W;
+    hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3((HW + 63) / 64, (p.KCp + 63) / 64, g.N), dim3(256), 0, st,
+                       (const bf16_t *)X, in, g.C, HW, p.KCp);
+    const long wtotal = (long)p.ntaps_total * p.Mp * p.KCp;
+    hipLaunchKernelGGL(filter_repack_kernel, dim3((unsigned)((wtotal + 255) / 256)), dim3(256), 0, st, (const bf16_t *)W, wt,
+                       g.K, g.C, p.ntaps_total, p.Mp, p.KCp, 0);
+    p.in = in; p.wt = wt; p.bias = (const bf16_t *)b; p.out = (bf16_t *)Y;
+    *err = run_gather(p, variant, st);
+    return true;
+}
+
+// Data gradient: dX = W^T * dY.  False when the geometry is not covered.
+bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,
+                    hipError_t *err)
+{
+    if (!supported(g, dtype)) return false;
+    GatherParams base{};
+    base.N = g.N; base.M = g.C; base.Mp = round_up(g.C, 64); base.KCp = round_up(g.K, 16);
+    base.Hin = g.P; base.Win = g.Q; base.Hout = g.H; base.Wout = g.W;
+    base.os = g.sh; base.is = 1; base.ntaps_total = g.R * g.S;
+    // plan every output parity class first so that nothing is launched if one does not fit
+    GatherParams cls[4];
+    int variant[4], ncls = 0;
+    bool empty_class = false;
+    for (int a0 = 0; a0 < g.sh; ++a0)
+        for (int b0 = 0; b0 < g.sw; ++b0) {
+            GatherParams p = base;
+            p.a0 = a0; p.b0 = b0;
+            p.Hc = (g.H - a0 + g.sh - 1) / g.sh;
+            p.Wc = (g.W - b0 + g.sw - 1) / g.sw;
+            if (p.Hc <= 0 || p.Wc <= 0) continue;
+            p.ntaps = 0;
+            for (int r = 0; r < g.R; ++r)
+                for (int s = 0; s < g.S; ++s) {
+                    const int th = a0 + g.ph - r, tw = b0 + g.pw - s;
+                    if (th % g.sh || tw % g.sw) continue; // C++ remainder: zero iff divisible, also for negatives
+                    p.dh[p.ntaps] = th / g.sh; p.dw[p.ntaps] = tw / g.sw; p.wtap[p.ntaps] = r * g.S + s;
+                    ++p.ntaps;
+                }
+            if (p.ntaps == 0) { empty_class = true; continue; }
+            if (!shape_gather(p, &variant[ncls])) return false;
+            cls[ncls++] = p;
+        }
+    const size_t in_bytes = ((size_t)g.N * g.P * g.Q * base.KCp * 2 + 255) / 256 * 256;
+    bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + in_bytes);
+    // pixels no output pixel's tap reaches (possible when stride > filter) stay zero
+    if (empty_class) {
+        // (a fill kernel, not a memset node: callers may capture this call in a HIP graph)
+        const long n16 = ((long)g.N * g.C * g.H * g.W * 2 + 15) / 16; // tensor allocations are 16-byte granular
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (u32x4 *)dX, n16);
+    }
+    const int PQ = g.P * g.Q;
+    hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3((PQ + 63) / 64, (base.KCp + 63) / 64, g.N), dim3(256), 0, st,
+                       (const bf16_t *)dY, in, g.K, PQ, base.KCp);
+    const long wtotal = (long)base.ntaps_total * base.Mp * base.KCp;
+    hipLaunchKernelGGL(filter_repack_kernel, dim3((unsigned)((wtotal + 255) / 256)), dim3(256), 0, st, (const bf16_t *)W, wt,
+                       g.K, g.C, base.ntaps_total, base.Mp, base.KCp, 1);
+    *err = hipGetLastError();
+    for (int k = 0; k < ncls && *err == hipSuccess; ++k) {
+        cls[k].in = in; cls[k].wt = wt; cls[k].bias = nullptr; cls[k].out = (bf16_t *)dX;
+        *err = run_gather(cls[k], variant[k], st);
+    }
+    return true;
+}
+
+} // namespace cac
