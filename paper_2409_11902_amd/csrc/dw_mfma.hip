@@ -468,11 +468,37 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
         seg = 0;                                                                                  \
         ++rp;                                                                                     \
     }
-        for (int t = 0;;) {
-            CAC_STEP(X, Y)
-            if (++t == nsteps) break;
-            CAC_STEP(Y, X)
-            if (++t == nsteps) break;
+        if constexpr (NPH == 1) {
+            for (int t = 0;;) {
+                CAC_STEP(X, Y)
+                if (++t == nsteps) break;
+                CAC_STEP(Y, X)
+                if (++t == nsteps) break;
+            }
+        } else {
+            // two column phases double the xhat operands: a second operand set does not
+            // fit the register file next to the accumulators, so these (few) layers
+            // request each step's operands right before using them
+            for (int t = 0; t < nsteps; ++t) {
+                mfma_step(X);
+                if (t + 1 == nsteps) break;
+                if (seg + 1 < segs) {
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) X.aw[mi].prev3 = X.aw[mi].blk[0][3];
+                    request(X, ra, rx, seg + 1, seg + 2 == segs);
+                    ++seg;
+                } else {
+                    ra = ac + 2 * e_next[0];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e_next[1 + r];
+                    e_next = *(const u32x4 *)(smem + tab + 32 * min(rp + 2, nrp - 1));
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) X.aw[mi].prev3 = 0;
+                    request(X, ra, rx, 0, segs == 1);
+                    seg = 0;
+                    ++rp;
+                }
+            }
         }
 #undef CAC_STEP
     };
