@@ -37,8 +37,11 @@ def parse():
     ap.add_argument("--layers", default="", help="comma-separated layer indices of the workload (default all)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default="", choices=["", "dw", "compress", "fwd", "dx"],
-                    help="profiling aid: run just this entry point --steps times per layer and exit")
+    ap.add_argument("--only", default="", choices=["", "dw", "compress", "fwd", "dx", "copy"],
+                    help="profiling aid: run just this entry point --steps times per layer and exit "
+                         "(copy: a plain 256 MiB device copy, the yardstick the HBM counters are scaled by)")
+    ap.add_argument("--also", default="cfg5_deep_small_spatial",
+                    help="second workload whose dW launches are timed too (reported under dw_other_workloads); '' for none")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -46,24 +49,33 @@ def parse():
 class Layer:
     """Device buffers of one layer of the workload."""
 
-    def __init__(self, spec, config, B, synth, torch):
+    def __init__(self, spec, config, B, synth, torch, dw_only=False):
         upload = B.to_device
         self.spec = spec
         self.d = B.desc_from_spec(spec)
         hp, wp, self.z_bytes, self.x_bytes = B.cac_pooled_shape(self.d)
-        t = synth.make_inputs(spec, config)
-        self.host = t
         td = torch.float32 if spec.dtype == synth.F32 else torch.bfloat16
         dev = "cuda:0"
-        self.X, self.W, self.b, self.dY = (upload(t[k], spec.dtype) for k in ("X", "W", "b", "dY"))
-        self.Y = torch.empty((spec.N, spec.K, spec.P, spec.Q), dtype=td, device=dev)
-        self.Z = torch.empty((spec.N, spec.C, hp, wp), dtype=td, device=dev)
-        self.dW = torch.empty((spec.K, spec.C, spec.R, spec.S), dtype=torch.float32, device=dev)
-        self.dX = torch.empty((spec.N, spec.C, spec.H, spec.W), dtype=td, device=dev)
         self.ws = {}
-        for op in (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA):
+        ops = (B.OP_BWD_WEIGHT_COMPRESSED,) if dw_only else (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA)
+        for op in ops:
             n = B.cac_workspace_size(self.d, op)
             self.ws[op] = torch.empty(max(n, 16), dtype=torch.uint8, device=dev) if n else None
+        self.Z = torch.empty((spec.N, spec.C, hp, wp), dtype=td, device=dev)
+        self.dW = torch.empty((spec.K, spec.C, spec.R, spec.S), dtype=torch.float32, device=dev)
+        if dw_only:
+            # only what the weight gradient reads: Z comes from the library's own compress pass
+            t = synth.make_inputs(spec, config, tensors=("X", "dY"))
+            X = upload(t["X"], spec.dtype)
+            self.dY = upload(t["dY"], spec.dtype)
+            B.cac_compress(self.d, X, self.Z, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            del X
+        else:
+            t = synth.make_inputs(spec, config)
+            self.X, self.W, self.b, self.dY = (upload(t[k], spec.dtype) for k in ("X", "W", "b", "dY"))
+            self.Y = torch.empty((spec.N, spec.K, spec.P, spec.Q), dtype=td, device=dev)
+            self.dX = torch.empty((spec.N, spec.C, spec.H, spec.W), dtype=td, device=dev)
         self.plan = B.cac_describe_plan(self.d, B.OP_BWD_WEIGHT_COMPRESSED)
         eb = spec.elem_bytes
         self.flops = {
@@ -91,6 +103,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.lib()  # fail loudly if the native library is missing
+    if args.only == "copy":
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup + args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"only": "copy", "bytes_read": src.numel(), "bytes_written": src.numel(),
+                          "calls": args.warmup + args.steps}))
+        return
     cfgs = synth.configs()
     specs = cfgs[args.workload]
     if args.layers:
@@ -167,7 +188,7 @@ def main():
 
     # ---- per-op durations with events on the launch stream (instrumented loop, eager)
     nrep = max(5, min(args.steps, 30))
-    names = ("fwd+compress", "dw", "dx")
+    names = ("fwd+compress", "dw_in_step", "dx")
     acc = {n: [0.0] * len(layers) for n in names}
     evs = []
     for _ in range(nrep):
@@ -185,6 +206,9 @@ def main():
     for i, e in evs:
         for j, n in enumerate(names):
             acc[n][i] += e[j].elapsed_time(e[j + 1]) / nrep  # ms
+
+    # ---- the weight-gradient call alone: back-to-back launches between two events on the launch stream
+    dw_ms = time_dw(layers, B, torch, stream)
 
     # ---- compress alone: warm (same buffers) and cold (rotating through > 512 MiB)
     comp = []
@@ -218,25 +242,27 @@ def main():
     # ---- report
     tot_flops = sum(sum(L.flops.values()) for L in layers)
     dw_flops = sum(L.flops["dw"] for L in layers)
-    dw_ms = sum(acc["dw"])
     log(f"[bench] {'layer':28s} {'fwd+cmp us':>10s} {'dW us':>8s} {'dW TF/s':>8s} {'%peak':>6s} {'dX us':>8s} "
         f"{'cmp cold GB/s':>13s} {'%hbm':>5s} {'warm GB/s':>9s} {'X MiB':>7s} {'Z MiB':>7s} {'saved':>6s}")
     per_layer = []
     for i, L in enumerate(layers):
-        dw_tf = L.flops["dw"] / (acc["dw"][i] * 1e-3) / 1e12
+        dw_tf = L.flops["dw"] / (dw_ms[i] * 1e-3) / 1e12
         warm, cold = comp[i]
         cg, wg = L.bytes["compress"] / (cold * 1e-3) / 1e9, L.bytes["compress"] / (warm * 1e-3) / 1e9
-        log(f"[bench] {L.spec.name:28s} {acc['fwd+compress'][i] * 1e3:10.1f} {acc['dw'][i] * 1e3:8.1f} {dw_tf:8.1f} "
+        log(f"[bench] {L.spec.name:28s} {acc['fwd+compress'][i] * 1e3:10.1f} {dw_ms[i] * 1e3:8.1f} {dw_tf:8.1f} "
             f"{100 * dw_tf / PEAK_BF16_TFLOPS:6.1f} {acc['dx'][i] * 1e3:8.1f} {cg:13.0f} {100 * cg / PEAK_HBM_GBPS:5.1f} "
             f"{wg:9.0f} {L.x_bytes / 2**20:7.2f} {L.z_bytes / 2**20:7.2f} {L.x_bytes / L.z_bytes:6.2f}")
-        per_layer.append({"layer": L.spec.name, "dw_us": round(acc["dw"][i] * 1e3, 2), "dw_tflops": round(dw_tf, 1),
+        per_layer.append({"layer": L.spec.name, "dw_us": round(dw_ms[i] * 1e3, 2), "dw_tflops": round(dw_tf, 1),
+                          "dw_in_step_us": round(acc["dw_in_step"][i] * 1e3, 2),
                           "fwd_compress_us": round(acc["fwd+compress"][i] * 1e3, 2), "dx_us": round(acc["dx"][i] * 1e3, 2),
                           "compress_cold_gbps": round(cg, 1), "compress_warm_gbps": round(wg, 1),
                           "x_bytes": L.x_bytes, "z_bytes": L.z_bytes})
-    dw_tflops = dw_flops / (dw_ms * 1e-3) / 1e12
+    dw_tflops = dw_flops / (sum(dw_ms) * 1e-3) / 1e12
     comp_bytes = sum(L.bytes["compress"] for L in layers)
     comp_cold_gbps = comp_bytes / (sum(c for _, c in comp) * 1e-3) / 1e9
     x_total, z_total = sum(L.x_bytes for L in layers), sum(L.z_bytes for L in layers)
+    nl = len(layers)
+    traffic = read_traffic(args.workload) if not args.layers else None
 
     out = {
         "metric": "dW TFLOP/s + compress GB/s (% of MI355X roofline); activation bytes saved",
@@ -250,47 +276,127 @@ def main():
         "dw_tflops": round(dw_tflops, 1), "dw_frac_of_bf16_peak": round(dw_tflops / PEAK_BF16_TFLOPS, 4),
         "compress_cold_gbps": round(comp_cold_gbps, 1), "compress_frac_of_hbm_peak": round(comp_cold_gbps / PEAK_HBM_GBPS, 4),
         "activation_bytes": {"x": x_total, "z": z_total, "saved": x_total - z_total, "ratio": round(x_total / z_total, 3)},
-        "roofline": {"kernel": "dw_mfma_kernel (+ slice reduction) via conv_bwd_weight_compressed", "bound": "mfma",
-                     "achieved": round(dw_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(dw_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                     "flops_per_launch": dw_flops // len(layers), "avg_launch_us": round(dw_ms * 1e3 / len(layers), 2)},
+        # one launch = one conv_bwd_weight_compressed call on one layer = dw_mfma_kernel plus the
+        # slice-sum kernel behind it; flops and duration are the means over the workload's layers
+        "roofline": {"kernel": "dw_mfma_kernel + dw_reduce (the two launches of conv_bwd_weight_compressed)",
+                     "bound": "mfma", "achieved": round(dw_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(dw_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                     "flops_per_launch": dw_flops // nl, "algorithmic_bytes_per_launch": sum(L.bytes["dw"] for L in layers) // nl,
+                     "avg_launch_us": round(sum(dw_ms) * 1e3 / nl, 2), "launches_timed": DW_LAUNCHES},
+        "roofline_compress": {"kernel": "compress_kernel (cac_compress, cold: inputs rotate through > 640 MB)",
+                              "bound": "hbm", "achieved": round(comp_cold_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                              "frac": round(comp_cold_gbps / PEAK_HBM_GBPS, 4),
+                              "bytes_per_launch": comp_bytes // nl,
+                              "avg_launch_us": round(sum(c for _, c in comp) * 1e3 / nl, 2)},
         "per_layer": per_layer,
     }
 
+    if args.also and args.also != args.workload and not args.layers:
+        del layers
+        torch.cuda.empty_cache()
+        other = [Layer(s, args.also, B, synth, torch, dw_only=True) for s in cfgs[args.also]]
+        oms = time_dw(other, B, torch, stream)
+        out["dw_other_workloads"] = {args.also: [
+            {"layer": L.spec.name, "dw_us": round(t * 1e3, 2), "dw_tflops": round(L.flops["dw"] / (t * 1e-3) / 1e12, 1),
+             "frac_of_bf16_peak": round(L.flops["dw"] / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)} for L, t in zip(other, oms)]}
+        for L, t in zip(other, oms):
+            log(f"[bench] {args.also} {L.spec.name}: dW {t * 1e3:.1f} us, "
+                f"{L.flops['dw'] / (t * 1e-3) / 1e12:.0f} TFLOP/s ({100 * L.flops['dw'] / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS:.1f}% of peak)")
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers[0], args.cpu_seconds, np)
+        out["cpu_baseline"] = cpu_baseline(specs, args.workload, synth, args.cpu_seconds, np)
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(L, seconds, np):
-    """The oracle as it stands, timed on this machine's host cores on a bounded sample:
-    pooling + inflation of the whole activation of the first layer, then as many
-    dW entries (full reduction length each) as fit the time budget."""
+DW_LAUNCHES = 200
+
+
+def time_dw(layers, B, torch, stream):
+    """Mean duration (ms) of one conv_bwd_weight_compressed call per layer: 20 untimed
+    launches, then DW_LAUNCHES back to back between two events recorded on the launch stream."""
+    out = []
+    for L in layers:
+        ws = L.ws[B.OP_BWD_WEIGHT_COMPRESSED]
+        for _ in range(20):
+            B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, ws, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(DW_LAUNCHES):
+            B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, ws, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1) / DW_LAUNCHES)
+    return out
+
+
+def read_traffic(workload):
+    """HBM bytes per conv_bwd_weight_compressed launch from the committed counter summary
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"dw_hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(float(line.split(":", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(specs, config, synth, seconds, np):
+    """The oracle as it stands, timed on this machine's host cores.  When a probe says
+    the whole step (every layer: pooling, inflation, forward, dW from the inflated map,
+    dX) fits the time budget, that is what runs; otherwise a sample of dW entries of the
+    first layer at full reduction length."""
     import oracle
-    spec = L.spec
-    g = oracle.ConvGeom(spec.N, spec.C, spec.K, spec.H, spec.W, spec.R, spec.S, spec.stride, spec.stride,
-                        spec.pad, spec.pad)
-    X, dY = L.host["X"].astype(np.float64), L.host["dY"].astype(np.float64)
-    t0 = time.perf_counter()
+
+    def geom(sp):
+        return oracle.ConvGeom(sp.N, sp.C, sp.K, sp.H, sp.W, sp.R, sp.S, sp.stride, sp.stride, sp.pad, sp.pad)
+
+    spec = specs[0]
+    host = synth.make_inputs(spec, config)
+    X, dY = host["X"].astype(np.float64), host["dY"].astype(np.float64)
     Xh = oracle.inflate(oracle.avgpool(X, spec.k, spec.k), spec.H, spec.W, spec.k, spec.k)
-    t_pool = time.perf_counter() - t0
     total = spec.K * spec.C * spec.R * spec.S
     rng = np.random.Generator(np.random.Philox(key=5))
     probe = rng.integers(0, total, 256)
     t0 = time.perf_counter()
-    oracle.conv_dw_entries(g, Xh, dY, probe)
+    oracle.conv_dw_entries(geom(spec), Xh, dY, probe)
     t_probe = time.perf_counter() - t0
+    flops_per_s = 2.0 * 256 * spec.N * spec.P * spec.Q / max(t_probe, 1e-9)
+    if 3 * spec.dw_flops / flops_per_s <= 2.5 * seconds:
+        # whole layers in order until the budget is spent (the probe's scattered entries
+        # run slower than whole tensors do, so this usually covers the whole workload)
+        t_total, flops, done = 0.0, 0, 0
+        for sp in specs:
+            if t_total > 2.5 * seconds:
+                break
+            done += 1
+            h = synth.make_inputs(sp, config)
+            X, W, b, dY = (h[k].astype(np.float64) for k in ("X", "W", "b", "dY"))
+            g = geom(sp)
+            t0 = time.perf_counter()
+            oracle.conv_fwd(g, X, W, b)
+            Xh = oracle.inflate(oracle.avgpool(X, sp.k, sp.k), sp.H, sp.W, sp.k, sp.k)
+            oracle.conv_dw(g, Xh, dY)
+            oracle.conv_dx(g, W, dY)
+            t_total += time.perf_counter() - t0
+            flops += 3 * sp.dw_flops
+        return {"value": round(flops / t_total / 1e12, 5),
+                "unit": "TFLOP/s (fwd + dW-from-Z + dX algorithmic flops of one step / step time)",
+                "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": f"one step over the first {done} of {len(specs)} layers of {config} (forward, pooling, "
+                          f"inflation, dW, dX of each whole layer), fp64 direct loops, {t_total:.1f}s"}
     n = int(min(total, max(256, 256 * seconds / max(t_probe, 1e-6))))
     idx = rng.integers(0, total, n)
     t0 = time.perf_counter()
-    oracle.conv_dw_entries(g, Xh, dY, idx)
+    oracle.conv_dw_entries(geom(spec), Xh, dY, idx)
     t_dw = time.perf_counter() - t0
     flops = 2.0 * n * spec.N * spec.P * spec.Q
     return {"value": round(flops / t_dw / 1e12, 5), "unit": "TFLOP/s (dW entries, fp64 direct loops)",
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{n} of {total} dW entries of layer {spec.name} at full reduction length "
-                      f"({t_dw:.1f}s; whole-layer dW extrapolates linearly to {t_dw * total / n:.0f}s); "
-                      f"pool+inflate of the whole activation {t_pool:.2f}s"}
+                      f"({t_dw:.1f}s; whole-layer dW extrapolates linearly to {t_dw * total / n:.0f}s)"}
 
 
 if __name__ == "__main__":

@@ -28,7 +28,6 @@ struct DwMfmaParams {
     int tile_o, tile_c;  // workgroup tile
     int tiles_o, tiles_c, total_wg;
     int direct;
-    int dbg;
 };
 
 struct DwMfmaPlan {

@@ -37,6 +37,20 @@
 #include "common.h"
 #include "dw_mfma.h"
 
+#ifdef CAC_TIMELINE
+__device__ long long cac_timeline[1024 * 16];
+extern "C" int cac_timeline_read(long long *host) { return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(cac_timeline), sizeof(long long) * 1024 * 16); }
+#define CAC_TL(slot) do { if ((threadIdx.x & 63) == 0 && v < 1024) cac_timeline[v * 16 + (slot)] = wall_clock64(); } while (0)
+#define CAC_TA_DECL long long ta_t = wall_clock64(), ta_acc[4] = {0, 0, 0, 0};
+#define CAC_TA(k) do { long long n_ = wall_clock64(); ta_acc[k] += n_ - ta_t; ta_t = n_; } while (0)
+#define CAC_TA_OUT(base) do { if ((threadIdx.x & 63) == 0 && v < 1024) { cac_timeline[v * 16 + (base)] = ta_acc[0]; cac_timeline[v * 16 + (base) + 1] = ta_acc[1]; cac_timeline[v * 16 + (base) + 2] = ta_acc[2]; if ((base) == 11) cac_timeline[v * 16 + 7] = ta_acc[3]; } } while (0)
+#else
+#define CAC_TL(slot) do {} while (0)
+#define CAC_TA_DECL
+#define CAC_TA(k) do {} while (0)
+#define CAC_TA_OUT(base) do {} while (0)
+#endif
+
 namespace cac {
 
 namespace {
@@ -56,6 +70,11 @@ template <int ha, int hb> __device__ __forceinline__ uint32_t halves(uint32_t a,
     constexpr uint32_t sel = (2 * ha) | ((2 * ha + 1) << 8) | ((4 + 2 * hb) << 16) | ((5 + 2 * hb) << 24);
     return __builtin_amdgcn_perm(b, a, sel);
 }
+
+// 16 bytes of LDS at an absolute LDS byte address (saves the compiler adding the
+// base of the dynamic LDS block, unknown until link time, to every access).
+typedef __attribute__((address_space(3))) const u32x4 *lds_u32x4_ptr;
+__device__ __forceinline__ u32x4 lds16(uint32_t addr) { return *(lds_u32x4_ptr)addr; }
 
 constexpr int kMaxDy = 8; // 16-byte dY items a thread moves per chunk
 constexpr int kMaxZ = 4;  // 16-byte Z items a thread moves per chunk
@@ -144,11 +163,14 @@ __device__ __forceinline__ u32x4 mask8(int left)
     return m;
 }
 
-template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN>
-__global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
+// SC: the number of 8-pixel segments per output row when it is known at compile
+// time (0: read from the plan).  With SC the walk along a row is unrolled and the
+// segment offsets become immediates of the LDS reads.
+template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS, int SC>
+__global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParams p)
 {
     constexpr int T = R * S;
-    constexpr int NT = 64 * WM * WN; // threads of each kind: MFMA waves, then as many copy waves
+    constexpr int NT = 64 * WM * WN * KS; // threads of each kind: MFMA waves, then as many copy waves
     constexpr int TILE_O = 32 * MI * WM, TILE_C = 32 * NI * WN;
     // floor division / remainder of (s - PAD) by SG for every filter column
     constexpr auto a_of = [](int s) { int d = s - PAD; return d >= 0 ? d / SG : -((-d + SG - 1) / SG); };
@@ -159,7 +181,6 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
     extern __shared__ __align__(16) unsigned char smem[];
     // [zero row][buffer 0: rows, sDY, sX][buffer 1: rows, sDY, sX]; offsets below are in
     // bf16 elements from the start of LDS, so offset 0 is the zero row
-    const bf16_t *sBase = (const bf16_t *)smem;
     bf16_t *sW = (bf16_t *)smem;
     const uint32_t rows_elems = p.LRpad * 8;                   // one 16-byte entry per row
     const uint32_t buf_elems = rows_elems + TILE_O * p.dy_ostride + TILE_C * p.x_cstride;
@@ -172,6 +193,7 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
     const int per_xcd = gridDim.x >> 3;
     const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (v >= p.total_wg) return;
+    if (threadIdx.x == 0) CAC_TL(0);
     const int ntiles = p.tiles_o * p.tiles_c;
     const int slice = v / ntiles, tile = v - slice * ntiles;
     const int ot = tile / p.tiles_c, ct = tile - ot * p.tiles_c;
@@ -335,29 +357,49 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
         };
 
         u32x4 dyA[kMaxDy], zA[kMaxZ], dyB[kMaxDy], zB[kMaxZ];
+        if (tid == 0) CAC_TL(8);
         if (ci_begin < ci_end) {
             fetch(ci_begin, dyA, zA);
             if (ci_begin + 1 < ci_end) fetch(ci_begin + 1, dyB, zB);
+            if (tid == 0) CAC_TL(9);
             stage(ci_begin, base0, dyA, zA);
         }
+        if (tid == 0) CAC_TL(10);
         __syncthreads(); // buffer 0 holds the first chunk
+        CAC_TA_DECL
         for (int ci = ci_begin; ci < ci_end; ci += 2) {
             // MFMA waves are on buffer 0 (chunk ci); set B holds chunk ci+1
             if (ci + 2 < ci_end) fetch(ci + 2, dyA, zA);
+            CAC_TA(0);
+#ifdef CAC_TIMELINE
+            __builtin_amdgcn_s_waitcnt(0xF7C); // vmcnt(12): everything but the fetch just issued has arrived
+            CAC_TA(3);
+#endif
             if (ci + 1 < ci_end) stage(ci + 1, base1, dyB, zB);
+            CAC_TA(1);
             __syncthreads();
+            CAC_TA(2);
             if (ci + 1 >= ci_end) break;
             // MFMA waves are on buffer 1 (chunk ci+1); set A holds chunk ci+2
             if (ci + 3 < ci_end) fetch(ci + 3, dyB, zB);
+            CAC_TA(0);
+#ifdef CAC_TIMELINE
+            __builtin_amdgcn_s_waitcnt(0xF7C);
+            CAC_TA(3);
+#endif
             if (ci + 2 < ci_end) stage(ci + 2, base0, dyA, zA);
+            CAC_TA(1);
             __syncthreads();
+            CAC_TA(2);
         }
+        if (tid == 0) CAC_TA_OUT(11);
+        if constexpr (KS > 1) __syncthreads(); // the barrier inside the MFMA waves' cross-wave sum
         return;
     }
 
     // =============================== MFMA waves ===========================================
     const int tid = threadIdx.x, lane = tid & 63, wave = wave_id;
-    const int wm = wave % WM, wn = wave / WM, half = lane >> 5, l32 = lane & 31;
+    const int wm = wave % WM, wn = (wave / WM) % WN, ks = wave / (WM * WN), half = lane >> 5, l32 = lane & 31;
 
     f32x16 acc[MI][NI][T];
 #pragma unroll
@@ -411,42 +453,85 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
     // Requests the operands of segment `seg` of the rows at byte addresses ra / rx[]
     // into `o`.  `tail`: the segment is the last of its row, nothing lies right of it.
     const uint32_t astep = 64 * p.dy_ostride, xstep = 64 * p.x_cstride, pw = 2 * p.PW;
-    auto request = [&](Ops &o, uint32_t ra, const uint32_t (&rx)[R], int seg, bool tail) {
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    auto request = [&](Ops &o, uint32_t ra, const uint32_t (&rx)[R], int seg, bool tail, const Ops *left = nullptr) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            o.aw[mi].blk[0] = *(const u32x4 *)(smem + ra + mi * astep + 16 * seg);
-            if constexpr (S > 1) // byte 0 of LDS starts the zero row
-                o.aw[mi].blk[1] = *(const u32x4 *)(smem + (tail ? 0u : ra + mi * astep + 16 * seg + 16));
+            // the block a step looks at to its right is the next step's own block
+            if (left && S > 1)
+                o.aw[mi].blk[0] = left->aw[mi].blk[1];
+            else
+                o.aw[mi].blk[0] = lds16(ra + mi * astep + 16 * seg);
+            if constexpr (S > 1) // the dynamic LDS block starts with the zero row
+                o.aw[mi].blk[1] = lds16(tail ? lds0 : ra + mi * astep + 16 * seg + 16);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int ph = 0; ph < NPH; ++ph)
-                    o.b[r][ni][ph] = *(const u32x4 *)(smem + rx[r] + ni * xstep + ph * pw + 16 * seg);
+                for (int ph = 0; ph < NPH; ++ph) o.b[r][ni][ph] = lds16(rx[r] + ni * xstep + ph * pw + 16 * seg);
     };
     auto compute = [&](uint32_t base) {
         // byte addresses in LDS of this lane's output channel / input channel
-        const uint32_t ac = 2 * (base + rows_elems + (wm * 32 * MI + l32) * p.dy_ostride);
-        const uint32_t xc = 2 * (base + rows_elems + TILE_O * p.dy_ostride + (wn * 32 * NI + l32) * p.x_cstride);
-        const uint32_t tab = 2 * base + half * 16; // row table, this half-wave's entries
-        const int nrp = p.LRpad / 2, segs = p.SEGS;
-        const int nsteps = nrp * segs;
+        const uint32_t ac = lds0 + 2 * (base + rows_elems + (wm * 32 * MI + l32) * p.dy_ostride);
+        const uint32_t xc = lds0 + 2 * (base + rows_elems + TILE_O * p.dy_ostride + (wn * 32 * NI + l32) * p.x_cstride);
+        const uint32_t tab = lds0 + 2 * base + half * 16; // row table, this half-wave's entries
+        // the KS waves that share a tile take every KS-th row pair each
+        const int nrp = p.LRpad / 2, segs = SC > 0 ? SC : p.SEGS;
+        const int nsteps = ((nrp - ks + KS - 1) / KS) * segs;
+        if (KS > 1 && nsteps == 0) return;
 
         // current rows of this lane and the raw table entry of the next row pair
-        u32x4 e = *(const u32x4 *)(smem + tab);
+        u32x4 e = lds16(tab + 32 * ks);
         uint32_t ra = ac + 2 * e[0], rx[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e[1 + r];
-        u32x4 e_next = *(const u32x4 *)(smem + tab + 32 * min(1, nrp - 1));
+        u32x4 e_next = lds16(tab + 32 * min(ks + KS, nrp - 1));
 
         Ops X, Y;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) X.aw[mi].prev3 = 0;
         request(X, ra, rx, 0, segs == 1);
 
-        int seg = 0, rp = 0;
+        if constexpr (SC > 0 && NPH == 1) {
+            // Row pairs as an outer loop, the SC segments of a row unrolled.  The operand sets
+            // alternate from step to step; an odd SC swaps their roles from one row to the next.
+            int rp = ks;
+#define CAC_ROW(A, B)                                                                               \
+    _Pragma("unroll") for (int sgi = 0; sgi < SC; ++sgi)                                            \
+    {                                                                                               \
+        Ops &use = (sgi & 1) ? B : A;                                                               \
+        Ops &get = (sgi & 1) ? A : B;                                                               \
+        if (sgi + 1 < SC) {                                                                         \
+            _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) get.aw[mi].prev3 = use.aw[mi].blk[0][3]; \
+            request(get, ra, rx, sgi + 1, sgi + 2 == SC, &use);                                     \
+        } else {                                                                                    \
+            ra = ac + 2 * e_next[0];                                                                \
+            _Pragma("unroll") for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e_next[1 + r];           \
+            e_next = lds16(tab + 32 * min(rp + 2 * KS, nrp - 1));                 \
+            _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) get.aw[mi].prev3 = 0;                 \
+            request(get, ra, rx, 0, SC == 1);                                                       \
+            rp += KS;                                                                               \
+        }                                                                                           \
+        mfma_step(use);                                                                             \
+        interleave();                                                                               \
+    }
+            const int nrows = nsteps / SC;
+            if constexpr (SC % 2 == 0) {
+                for (int i = 0; i < nrows; ++i) { CAC_ROW(X, Y) }
+            } else {
+                for (int i = 0;;) {
+                    CAC_ROW(X, Y)
+                    if (++i == nrows) break;
+                    CAC_ROW(Y, X)
+                    if (++i == nrows) break;
+                }
+            }
+#undef CAC_ROW
+            return;
+        }
+        int seg = 0, rp = ks;
         // One step: MFMAs on USE, operands of the following step requested into GET
         // (same rows one segment to the right, or the next row pair, whose table
         // entry was requested a row pair ago).
@@ -460,13 +545,13 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
     } else {                                                                                      \
         ra = ac + 2 * e_next[0];                                                                  \
         _Pragma("unroll") for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e_next[1 + r];             \
-        e_next = *(const u32x4 *)(smem + tab + 32 * min(rp + 2, nrp - 1));                        \
+        e_next = lds16(tab + 32 * min(rp + 2 * KS, nrp - 1));                   \
         _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) GET.aw[mi].prev3 = 0;                   \
         request(GET, ra, rx, 0, segs == 1);                                                       \
         mfma_step(USE);                                                                           \
         interleave();                                                                             \
         seg = 0;                                                                                  \
-        ++rp;                                                                                     \
+        rp += KS;                                                                                 \
     }
         if constexpr (NPH == 1) {
             for (int t = 0;;) {
@@ -491,49 +576,53 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
                     ra = ac + 2 * e_next[0];
 #pragma unroll
                     for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e_next[1 + r];
-                    e_next = *(const u32x4 *)(smem + tab + 32 * min(rp + 2, nrp - 1));
+                    e_next = lds16(tab + 32 * min(rp + 2 * KS, nrp - 1));
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi) X.aw[mi].prev3 = 0;
                     request(X, ra, rx, 0, segs == 1);
                     seg = 0;
-                    ++rp;
+                    rp += KS;
                 }
             }
         }
 #undef CAC_STEP
     };
 
+    if (tid == 0) CAC_TL(1);
     __syncthreads(); // buffer 0 holds the first chunk
+    if (tid == 0) CAC_TL(2);
+    CAC_TA_DECL
     for (int ci = ci_begin; ci < ci_end; ci += 2) {
-        if (!(p.dbg & 2)) compute(base0);
+        compute(base0);
+        CAC_TA(0);
+        if (tid == 0 && ci == ci_begin) CAC_TL(3);
         __syncthreads();
+        CAC_TA(1);
+        if (tid == 0 && ci == ci_begin) CAC_TL(4);
         if (ci + 1 >= ci_end) break;
-        if (!(p.dbg & 2)) compute(base1);
+        compute(base1);
+        CAC_TA(0);
         __syncthreads();
+        CAC_TA(1);
     }
+    if (tid == 0) CAC_TL(5);
+    if (tid == 0) CAC_TA_OUT(14);
 
     // ---- epilogue --------------------------------------------------------------------
-    // accumulator register j of lane l holds row 8*(j/4) + 4*(l/32) + j%4, column l%32
-    if (p.direct) {
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int c = c0 + (wn * NI + ni) * 32 + l32;
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int o = o0 + (wm * MI + mi) * 32 + 8 * (j / 4) + 4 * half + (j % 4);
-                    if (o < p.K && c < p.C) {
-                        float *dst = p.out + ((long)o * p.C + c) * T;
-#pragma unroll
-                        for (int t = 0; t < T; ++t) dst[t] = acc[mi][ni][t][j];
-                    }
-                }
-            }
-    } else {
-        // partial sums in fragment order: [slice][tile][wave][mi][ni][tap][j/4][lane][j%4]
-        typedef __attribute__((ext_vector_type(4))) float f32x4;
-        f32x4 *dst = (f32x4 *)p.out + (((long)slice * ntiles + tile) * (WM * WN) + wave) * (MI * NI * T * 4 * 64) + lane;
+    // accumulator register j of lane l holds row 8*(j/4) + 4*(l/32) + j%4, column l%32.
+    // The accumulators are handled as G groups of 4 registers: g = ((mi*NI + ni)*T + tap)*4 + j/4.
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    typedef f32x4 __attribute__((aligned(4))) f32x4_u;
+    constexpr int G = MI * NI * T * 4;
+    static_assert(KS == 1 || KS == 2 || KS == 4, "the K-split waves share the four row groups");
+    // The KS waves of a tile hold sums over different pixels.  Wave ks keeps the groups with
+    // j/4 in [ks*4/KS, (ks+1)*4/KS) and hands the others over through LDS (the staging buffers
+    // are dead: the loop above ends with a barrier), then adds what the other waves hand it, in
+    // wave order.  red[wm, wn][source wave][g][lane].
+    f32x4 *red = (f32x4 *)smem + ((wn * WM + wm) * KS) * (G * 64) + lane;
+#define CAC_GROUP(mi, ni, t, jq) \
+    f32x4 { acc[mi][ni][t][4 * (jq)], acc[mi][ni][t][4 * (jq) + 1], acc[mi][ni][t][4 * (jq) + 2], acc[mi][ni][t][4 * (jq) + 3] }
+    if constexpr (KS > 1) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -541,12 +630,56 @@ __global__ void __launch_bounds__(128 * WM * WN) dw_mfma_kernel(DwMfmaParams p)
 #pragma unroll
                 for (int t = 0; t < T; ++t)
 #pragma unroll
-                    for (int jq = 0; jq < 4; ++jq) {
-                        const f32x16 &a16 = acc[mi][ni][t];
-                        dst[(((mi * NI + ni) * T + t) * 4 + jq) * 64] =
-                            f32x4{a16[4 * jq], a16[4 * jq + 1], a16[4 * jq + 2], a16[4 * jq + 3]};
-                    }
+                    for (int jq = 0; jq < 4; ++jq)
+                        if (jq * KS / 4 != ks) red[(ks * G + ((mi * NI + ni) * T + t) * 4 + jq) * 64] = CAC_GROUP(mi, ni, t, jq);
+        __syncthreads();
     }
+    // partial sums in fragment order: [slice][tile][wm, wn][g][lane][j%4]
+    f32x4 *part = (f32x4 *)p.out + (((long)slice * ntiles + tile) * (WM * WN) + wn * WM + wm) * (G * 64) + lane;
+    const bool inside = o0 + TILE_O <= p.K && c0 + TILE_C <= p.C; // no edge of dW crosses the tile
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int jq = 0; jq < 4; ++jq) {
+                if (KS > 1 && jq * KS / 4 != ks) continue;
+                f32x4 v[T];
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    v[t] = CAC_GROUP(mi, ni, t, jq);
+                    if constexpr (KS > 1) {
+#pragma unroll
+                        for (int k2 = 0; k2 < KS; ++k2)
+                            if (k2 != ks) v[t] += red[(k2 * G + ((mi * NI + ni) * T + t) * 4 + jq) * 64];
+                    }
+                }
+                if (!p.direct) {
+#pragma unroll
+                    for (int t = 0; t < T; ++t) part[(((mi * NI + ni) * T + t) * 4 + jq) * 64] = v[t];
+                    continue;
+                }
+                // dW itself: the T taps of one (o, c) are consecutive floats
+                const int c = c0 + (wn * NI + ni) * 32 + l32;
+                const int ob = o0 + (wm * MI + mi) * 32 + 8 * jq + 4 * half;
+                float *dst = p.out + ((long)ob * p.C + c) * T;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (inside || (ob + e < p.K && c < p.C)) {
+                        float *d = dst + (long)e * p.C * T;
+                        if constexpr (T == 9) {
+                            *(f32x4_u *)d = f32x4{v[0][e], v[1][e], v[2][e], v[3][e]};
+                            *(f32x4_u *)(d + 4) = f32x4{v[4][e], v[5][e], v[6][e], v[7][e]};
+                            d[8] = v[8][e];
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < T; ++t) d[t] = v[t][e];
+                        }
+                    }
+                }
+            }
+#undef CAC_GROUP
+    if (tid == 0) CAC_TL(6);
 }
 
 // Sums the slices' partial tiles in slice order and writes dW in its own layout.
@@ -670,66 +803,70 @@ int largest_vec(int extent, int cap)
 
 // Kernel table: filter/stride family x workgroup shape.
 struct Variant {
-    int R, SG, MI, NI, WM, WN;
+    int R, SG, MI, NI, WM, WN, KS;
     hipError_t (*launch)(const DwMfmaParams &, dim3, hipStream_t);
 };
 
-template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN>
-hipError_t launch_variant(const DwMfmaParams &p, dim3 grid, hipStream_t st)
+template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS, int SC>
+hipError_t launch_fixed(const DwMfmaParams &p, dim3 grid, hipStream_t st)
 {
-    auto kern = dw_mfma_kernel<R, S, SG, PAD, MI, NI, WM, WN>;
+    auto kern = dw_mfma_kernel<R, S, SG, PAD, MI, NI, WM, WN, KS, SC>;
     static bool attr_set = false; // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(128 * WM * WN), p.lds_bytes, st, p);
+    hipLaunchKernelGGL(kern, grid, dim3(128 * WM * WN * KS), p.lds_bytes, st, p);
     return hipGetLastError();
+}
+// Picks the instantiation with the row length built in when there is one.
+template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS>
+hipError_t launch_variant(const DwMfmaParams &p, dim3 grid, hipStream_t st)
+{
+    if constexpr (S == 3 && SG == 1) {
+        switch (p.SEGS) {
+        case 1: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 1>(p, grid, st);
+        case 2: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 2>(p, grid, st);
+        case 4: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 4>(p, grid, st);
+        case 7: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 7>(p, grid, st);
+        default: break;
+        }
+    }
+    return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 0>(p, grid, st);
 }
 
 const Variant kVariants[] = {
-    {3, 1, 1, 1, 2, 2, launch_variant<3, 3, 1, 1, 1, 1, 2, 2>}, // 3x3: 64 x 64 tile, 144 accumulators per wave
-    {3, 2, 1, 1, 2, 2, launch_variant<3, 3, 2, 1, 1, 1, 2, 2>},
-    {1, 1, 2, 2, 2, 2, launch_variant<1, 1, 1, 0, 2, 2, 2, 2>}, // 1x1: 128 x 128 tile
-    {1, 1, 2, 2, 1, 1, launch_variant<1, 1, 1, 0, 2, 2, 1, 1>}, // 1x1:  64 x 64 tile, one wave
-    {1, 2, 2, 2, 2, 2, launch_variant<1, 1, 2, 0, 2, 2, 2, 2>},
-    {1, 2, 2, 2, 1, 1, launch_variant<1, 1, 2, 0, 2, 2, 1, 1>},
+    {3, 1, 1, 1, 2, 2, 1, launch_variant<3, 3, 1, 1, 1, 1, 2, 2, 1>}, // 3x3: 64 x 64 tile, 144 accumulators per wave
+    {3, 1, 1, 1, 1, 1, 4, launch_variant<3, 3, 1, 1, 1, 1, 1, 1, 4>}, // 3x3: 32 x 32 tile, the pixels split over 4 waves
+    {3, 2, 1, 1, 2, 2, 1, launch_variant<3, 3, 2, 1, 1, 1, 2, 2, 1>},
+    {3, 2, 1, 1, 1, 1, 4, launch_variant<3, 3, 2, 1, 1, 1, 1, 1, 4>},
+    {1, 1, 2, 2, 2, 2, 1, launch_variant<1, 1, 1, 0, 2, 2, 2, 2, 1>}, // 1x1: 128 x 128 tile
+    {1, 1, 2, 2, 1, 1, 4, launch_variant<1, 1, 1, 0, 2, 2, 1, 1, 4>}, // 1x1:  64 x 64 tile, the pixels split over 4 waves
+    {1, 1, 2, 2, 1, 1, 1, launch_variant<1, 1, 1, 0, 2, 2, 1, 1, 1>}, // 1x1:  64 x 64 tile, one wave
+    {1, 2, 2, 2, 2, 2, 1, launch_variant<1, 1, 2, 0, 2, 2, 2, 2, 1>},
+    {1, 2, 2, 2, 1, 1, 4, launch_variant<1, 1, 2, 0, 2, 2, 1, 1, 4>},
+    {1, 2, 2, 2, 1, 1, 1, launch_variant<1, 1, 2, 0, 2, 2, 1, 1, 1>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 } // namespace
 
-bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
+namespace {
+
+// The plan for one entry of the kernel table; false when the geometry does not fit it.
+bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
 {
-    if (dtype != CAC_BF16) return false;
-    if (g.R != g.S || g.sh != g.sw || g.ph != g.pw) return false;
-    const bool f3 = g.R == 3 && g.ph == 1, f1 = g.R == 1 && g.ph == 0;
-    if (!(f3 || f1) || (g.sh != 1 && g.sh != 2)) return false;
     auto log2_of = [](int k) { return k == 1 ? 0 : k == 2 ? 1 : k == 4 ? 2 : k == 8 ? 3 : -1; };
     const int khl = log2_of(g.kh), kwl = log2_of(g.kw);
-    if (khl < 0 || kwl < 0) return false;
-    if (g.Q > 256 || g.W > 1024) return false;
-    // buffer loads address with 32-bit byte offsets and use 2^31 as "no load"
-    if ((long)g.N * g.K * g.P * g.Q >= (1L << 30) || (long)g.N * g.C * g.Hp * g.Wp >= (1L << 30)) return false;
     const int T = g.R * g.S;
-
-    // workgroup shape: the large tile unless it would be mostly padding
-    int vi = -1;
-    for (int i = 0; i < kNumVariants; ++i) {
-        const Variant &v = kVariants[i];
-        if (v.R != g.R || v.SG != g.sh) continue;
-        const int to = 32 * v.MI * v.WM, tc = 32 * v.NI * v.WN;
-        const bool big = to > 64;
-        if (big && (g.K <= to / 2 || g.C <= tc / 2)) continue;
-        vi = i;
-        break;
-    }
-    if (vi < 0) return false;
     const Variant &var = kVariants[vi];
-    const int NT = 64 * var.WM * var.WN;
+    const int KS = var.KS;
+    const int NT = 64 * var.WM * var.WN * KS;
     const int tile_o = 32 * var.MI * var.WM, tile_c = 32 * var.NI * var.WN;
     const int lds_budget = (NT == 256 ? 156 : NT == 128 ? 78 : 39) * 1024; // whole CU / half / quarter
+    const int groups = var.MI * var.NI * T * 4;                             // accumulator groups of 4 per wave
+    const int red_bytes = KS > 1 ? var.WM * var.WN * KS * groups * 64 * 16 : 0;
 
     DwMfmaParams base{};
     base.N = g.N; base.C = g.C; base.K = g.K; base.H = g.H; base.W = g.W; base.P = g.P; base.Q = g.Q;
@@ -778,7 +915,9 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
         q.dy_ostride = 8 * ((q.rowitems + 1) | 1); // + one block: the dY window looks one block past a row
         q.x_cstride = 8 * (((nbi * nz + 1) * (q.XW / 8)) | 1); // + the zero slot
         q.lds_bytes = (q.XW + 2 * (q.LRpad * 8 + tile_o * q.dy_ostride + tile_c * q.x_cstride)) * 2;
-        return q.lds_bytes <= lds_budget;
+        if (q.lds_bytes > lds_budget) return false;
+        q.lds_bytes = max(q.lds_bytes, red_bytes); // the cross-wave sum reuses the staging space
+        return true;
     };
     // Candidates: part of one image (nbi = 1, pr <= P) or several whole images.
     // Cost = MFMA steps spent per useful pixel row, then prefer longer chunks.
@@ -787,9 +926,10 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
     auto consider = [&](int nbi, int pr) {
         DwMfmaParams q;
         if (!shape(nbi, pr, q)) return;
-        const double steps = (double)q.RB * (q.LRpad / 2) * q.SEGS;      // per group of nbi images
+        const int rp_wave = (q.LRpad / 2 + KS - 1) / KS;                 // row pairs of the busiest wave
+        const double steps = (double)q.RB * rp_wave * KS * q.SEGS;       // per group of nbi images
         const double useful = (double)nbi * g.P * g.Q / 16.0;
-        const double per_chunk = (q.LRpad / 2) * q.SEGS;
+        const double per_chunk = rp_wave * q.SEGS;
         const double cost = steps / useful * (1.0 + 1.5 / per_chunk);     // barrier + refill share
         if (cost < best_cost) { best_cost = cost; best = q; }
     };
@@ -827,13 +967,50 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
     return true;
 }
 
+} // namespace
+
+bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
+{
+    if (dtype != CAC_BF16) return false;
+    if (g.R != g.S || g.sh != g.sw || g.ph != g.pw) return false;
+    const bool f3 = g.R == 3 && g.ph == 1, f1 = g.R == 1 && g.ph == 0;
+    if (!(f3 || f1) || (g.sh != 1 && g.sh != 2)) return false;
+    auto log2_of = [](int k) { return k == 1 ? 0 : k == 2 ? 1 : k == 4 ? 2 : k == 8 ? 3 : -1; };
+    const int khl = log2_of(g.kh), kwl = log2_of(g.kw);
+    if (khl < 0 || kwl < 0) return false;
+    if (g.Q > 256 || g.W > 1024) return false;
+    // buffer loads address with 32-bit byte offsets and use 2^31 as "no load"
+    if ((long)g.N * g.K * g.P * g.Q >= (1L << 30) || (long)g.N * g.C * g.Hp * g.Wp >= (1L << 30)) return false;
+
+    // Workgroup shape.  Splitting the pixels over the waves of a workgroup (KS > 1) cuts the
+    // partial sums a workgroup writes by KS at the price of shorter runs between barriers and
+    // twice the staging work per MFMA; it pays when a workgroup has only a few chunks to go
+    // through.  Among the others: the large tile unless it would be mostly padding.
+    DwMfmaPlan whole, split;
+    bool have_whole = false, have_split = false;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.R != g.R || v.SG != g.sh) continue;
+        const int to = 32 * v.MI * v.WM, tc = 32 * v.NI * v.WN;
+        if (to > 64 && (g.K <= to / 2 || g.C <= tc / 2)) continue;
+        if (v.KS > 1) {
+            if (!have_split) have_split = plan_with(g, i, &split);
+        } else {
+            if (!have_whole) have_whole = plan_with(g, i, &whole);
+        }
+    }
+    if (!have_whole && !have_split) return false;
+    const bool use_split = have_split && (!have_whole || split.p.chunks_per_slice <= 12);
+    *plan = use_split ? split : whole;
+    return true;
+}
+
 hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY, float *dW, void *ws, hipStream_t st)
 {
     DwMfmaParams p = plan.p;
     p.Z = (const bf16_t *)Z;
     p.dY = (const bf16_t *)dY;
     p.out = p.direct ? dW : (float *)ws;
-    if (const char *e = getenv("CAC_DW_DEBUG")) p.dbg = atoi(e);
     const Variant &var = kVariants[plan.variant];
     hipError_t e = var.launch(p, dim3(plan.grid), st);
     if (e != hipSuccess || p.direct) return e;
@@ -841,8 +1018,8 @@ hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY,
     const long per_slice = plan.tile_elems * p.tiles_o * p.tiles_c;
     // thread rows over the slices: enough of them to keep a few hundred thousand loads in flight
     const long cols = per_slice / 4;
-    if (p.nslices <= 8 && cols >= (1 << 16)) {
-        const unsigned blocks = (unsigned)(per_slice / (1024 * rs.T));
+    const unsigned blocks = (unsigned)(per_slice / (1024 * rs.T)); // of the whole-row kernel
+    if (p.nslices <= 8 && blocks >= 256) {
         if (rs.T == 9)
             hipLaunchKernelGGL(dw_reduce_tile_kernel<9>, dim3(blocks), dim3(256), 0, st, (const float *)ws, dW, rs);
         else
