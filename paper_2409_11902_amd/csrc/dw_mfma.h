@@ -23,7 +23,7 @@ struct DwMfmaParams {
     int dy_ostride, x_cstride;    // LDS elements per output channel / per input channel
     int lds_bytes;
     int dy_vec, z_vec;   // widest aligned global vector (elements)
-    uint32_t m_segs, m_pr, m_zv, m_nz;
+    uint32_t m_segs, m_pr, m_zv, m_nz, m_rb;
     int nchunks, chunks_per_slice, nslices;
     int tile_o, tile_c;  // workgroup tile
     int tiles_o, tiles_c, total_wg;

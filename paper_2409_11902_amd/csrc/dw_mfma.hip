@@ -242,39 +242,66 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         const bool ragged = (p.W & ((1 << p.kw_log2) - 1)) != 0; // the last pooling tile reaches past W
         const rsrc_t rs_dy = make_rsrc(p.dY, (uint32_t)p.N * p.K * p.P * p.Q * 2u);
         const rsrc_t rs_z = make_rsrc(p.Z, (uint32_t)p.N * p.C * p.Hp * p.Wp * 2u);
-        const int olim = p.K - o0 - (int)dyo; // pass i holds a real output channel when i*opp < olim
-        const int clim = p.C - c0 - (int)zc;
+        // Output channels past K and input channels past C of an edge tile are read like any
+        // other (from whatever follows in the tensor, zeros past its end): they only reach
+        // accumulators that are never written out.
 
-        // element offsets of this thread's first dY / Z item of chunk ci, and whether it exists
-        struct Src { uint32_t dy, z; bool dy_ok, z_ok; int zbase, n0, p0; };
+        // What depends on the chunk is uniform over the workgroup: the first image and output
+        // row, the first Z row kept, and the element offsets of the tile's first dY / Z element.
+        struct Src { uint32_t dy, z; int zbase, n0, p0; };
         auto src_of = [&](int ci) {
             Src s;
-            const int ig = ci / p.RB, rb = ci - ig * p.RB;
+            const int ig = fdiv(ci, p.m_rb), rb = ci - ig * p.RB;
             s.n0 = ig * p.NBI;
             s.p0 = rb * p.PR;
             s.zbase = max(0, (s.p0 * SG - PAD) >> p.kh_log2);
-            s.dy_ok = dy_real && s.n0 + (int)dy_ni < p.N && s.p0 + (int)dy_pr < p.P;
-            s.dy = ((uint32_t)(s.n0 * p.K + o0) * p.P + s.p0) * p.Q + dy_rel;
-            s.z_ok = z_write && s.n0 + (int)z_ni < p.N && s.zbase + (int)z_sl < p.Hp;
-            s.z = ((uint32_t)(s.n0 * p.C + c0) * p.Hp + s.zbase) * p.Wp + z_rel;
+            s.dy = ((uint32_t)(s.n0 * p.K + o0) * p.P + s.p0) * p.Q;
+            s.z = ((uint32_t)(s.n0 * p.C + c0) * p.Hp + s.zbase) * p.Wp;
             return s;
         };
-        // ---- global -> registers for one chunk
-        auto fetch = [&](int ci, u32x4 (&rdy)[kMaxDy], u32x4 (&rz)[kMaxZ]) {
+        // Element offset of this lane's item within the chunk, or far outside the tensor
+        // (2^30 elements: the byte offset stays in [2^31, 2^32) after every addition below)
+        // for a lane without an item.
+        constexpr uint32_t kNoElem = 0x40000000u;
+        const uint32_t dy_lane = dy_real ? dy_rel : kNoElem, z_lane = z_write ? z_rel : kNoElem;
+        const uint32_t dy_istep = dy_gstep, z_istep = z_gstep;
+        // ---- global -> registers for one chunk: one add per item, no branch
+        // `live` false (uniform): the chunk does not exist; the loads are issued all the same,
+        // past the tensors, so that the number of loads in flight is the same on every path and
+        // a wait for the older chunk never has to include the younger one.
+        auto fetch = [&](int ci, bool live, u32x4 (&rdy)[kMaxDy], u32x4 (&rz)[kMaxZ]) {
             const Src s = src_of(ci);
+            // rows past P and images past N of an edge chunk must read as zeros: their pixels
+            // meet real xhat rows in the shifted windows of their neighbours
+            const bool dy_in = live && s.n0 + (int)dy_ni < p.N && s.p0 + (int)dy_pr < p.P;
+            const uint32_t e_dy = dy_in ? s.dy + dy_lane : kNoElem;
+            const uint32_t e_z = live ? s.z + z_lane : kNoElem; // rows past Hp are never looked at
 #pragma unroll
-            for (int i = 0; i < kMaxDy; ++i)
-                rdy[i] = load_raw8(rs_dy, s.dy + i * dy_gstep, i < p.dy_passes && s.dy_ok && (int)(i * dy_opp) < olim);
+            for (int i = 0; i < kMaxDy; ++i) {
+                // items past the last pass: offset 2^30 elements as well (uniform select)
+                const uint32_t e = e_dy + (i < p.dy_passes ? i * dy_istep : kNoElem);
+                rdy[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, (e & ~1u) * 2u, 0, 0);
+            }
 #pragma unroll
-            for (int i = 0; i < kMaxZ; ++i)
-                rz[i] = load_raw8(rs_z, s.z + i * z_gstep, i < p.z_passes && s.z_ok && (int)(i * z_cpp) < clim);
+            for (int i = 0; i < kMaxZ; ++i) {
+                const uint32_t e = e_z + (i < p.z_passes ? i * z_istep : kNoElem);
+                rz[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_z, (e & ~1u) * 2u, 0, 0);
+            }
         };
+        // masks of the ragged case for the two blocks an item expands to when f_log2 <= 1
+        u32x4 rag[2][2];
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                rag[ph][h] = mask8((p.W - ph + SG - 1) / SG - (int)(z_zv << (3 + max(f_log2, 0))) - 8 * h);
+        const int cw = __builtin_amdgcn_readfirstlane(tid >> 6); // index among the copy waves
         // ---- registers -> LDS buffer at element offset `base` (with the horizontal inflation)
         auto stage = [&](int ci, uint32_t base, const u32x4 (&rdy)[kMaxDy], const u32x4 (&rz)[kMaxZ]) {
             const Src s = src_of(ci);
             // row table: entry rho = {dY row offset, xhat row offset per filter row (the zero
             // slot for rows outside the image)}, in elements from the lane's channel base
-            if (tid < p.LRpad) {
+            if (cw == 0 && tid < p.LRpad) {
                 const uint32_t rho = tid;
                 const uint32_t ni = fdiv(rho, p.m_pr);
                 const int pp = s.p0 + (int)(rho - ni * p.PR);
@@ -289,24 +316,44 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                 }
                 *(u32x4 *)(sW + base + rho * 8) = e;
             }
+            // dY: fix-ups for all items first (they exchange data between lanes), then one
+            // predicated run of stores
+            u32x4 val[kMaxDy];
+            if (dy_odd) {
 #pragma unroll
-            for (int i = 0; i < kMaxDy; ++i)
-                if (i < p.dy_passes) { // (uniform; fix8 exchanges data between lanes)
-                    const u32x4 val = fix8(rdy[i], s.dy + i * dy_gstep, dy_mask, dy_odd);
-                    if (dy_write) *(u32x4 *)(sW + base + dy_lds + i * dy_lstep) = val;
-                }
-            {
+                for (int i = 0; i < kMaxDy; ++i) val[i] = fix8(rdy[i], s.dy + dy_rel + i * dy_istep, dy_mask, true);
+            } else {
+#pragma unroll
+                for (int i = 0; i < kMaxDy; ++i) val[i] = rdy[i] & dy_mask;
+            }
+            if (dy_write) {
+                bf16_t *d = sW + base + dy_lds;
+#pragma unroll
+                for (int i = 0; i < kMaxDy; ++i)
+                    if (i < p.dy_passes) *(u32x4 *)(d + i * dy_lstep) = val[i];
+            }
+            // Z
+            u32x4 zz[kMaxZ];
+            if (z_odd) {
+#pragma unroll
+                for (int i = 0; i < kMaxZ; ++i) zz[i] = fix8(rz[i], s.z + z_rel + i * z_istep, z_mask, true);
+            } else {
+#pragma unroll
+                for (int i = 0; i < kMaxZ; ++i) zz[i] = rz[i] & z_mask;
+            }
+            if (z_write) {
+                bf16_t *zd = sW + base + z_lds;
                 // Writes 8 elements of phase ph starting at element j; in the ragged case the
                 // elements whose xhat column SG*j+ph is at or beyond W are zeroed.
                 auto put8 = [&](bf16_t *dst, int ph, int j, u32x4 x) {
                     if (ragged) x &= mask8((p.W - ph + SG - 1) / SG - j);
-                    if (z_write) *(u32x4 *)(dst + ph * p.PW + j) = x;
+                    *(u32x4 *)(dst + ph * p.PW + j) = x;
                 };
 #define CAC_Z_ITEMS(...)                                                                           \
     _Pragma("unroll") for (int i = 0; i < kMaxZ; ++i) if (i < p.z_passes)                          \
     {                                                                                              \
-        const u32x4 z = fix8(rz[i], s.z + i * z_gstep, z_mask, z_odd);                             \
-        bf16_t *dst = sW + base + z_lds + i * z_lstep;                                             \
+        const u32x4 z = zz[i];                                                                     \
+        bf16_t *dst = zd + i * z_lstep;                                                            \
         /* pooled value k of the item in both halves of a dword */                                 \
         auto dup = [&](int k) { return (k & 1) ? halves<1, 1>(z[k >> 1], z[k >> 1]) : halves<0, 0>(z[k >> 1], z[k >> 1]); }; \
         (void)dup;                                                                                 \
@@ -317,22 +364,22 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                     // (zeros past W come from the load)
                     const int j0 = z_zv * 4;
                     CAC_Z_ITEMS({
-                        if (z_write) *(u32x2 *)(dst + j0) = u32x2{halves<0, 0>(z[0], z[1]), halves<0, 0>(z[2], z[3])};
-                        if (z_write && NPH > 1)
-                            *(u32x2 *)(dst + p.PW + j0) = u32x2{halves<1, 1>(z[0], z[1]), halves<1, 1>(z[2], z[3])};
+                        *(u32x2 *)(dst + j0) = u32x2{halves<0, 0>(z[0], z[1]), halves<0, 0>(z[2], z[3])};
+                        if (NPH > 1) *(u32x2 *)(dst + p.PW + j0) = u32x2{halves<1, 1>(z[0], z[1]), halves<1, 1>(z[2], z[3])};
                     })
                 } else if (f_log2 == 0) {
                     const int j0 = z_zv * 8;
                     CAC_Z_ITEMS({
-                        _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) put8(dst, ph, j0, z);
+                        _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph)
+                            *(u32x4 *)(dst + ph * p.PW + j0) = ragged ? z & rag[ph][0] : z;
                     })
                 } else if (f_log2 == 1) {
                     const int j0 = z_zv * 16;
                     CAC_Z_ITEMS({
                         const u32x4 lo = {dup(0), dup(1), dup(2), dup(3)}, hi = {dup(4), dup(5), dup(6), dup(7)};
                         _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) {
-                            put8(dst, ph, j0, lo);
-                            put8(dst, ph, j0 + 8, hi);
+                            *(u32x4 *)(dst + ph * p.PW + j0) = ragged ? lo & rag[ph][0] : lo;
+                            *(u32x4 *)(dst + ph * p.PW + j0 + 8) = ragged ? hi & rag[ph][1] : hi;
                         }
                     })
                 } else if (f_log2 == 2) {
@@ -358,18 +405,16 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
 
         u32x4 dyA[kMaxDy], zA[kMaxZ], dyB[kMaxDy], zB[kMaxZ];
         if (tid == 0) CAC_TL(8);
-        if (ci_begin < ci_end) {
-            fetch(ci_begin, dyA, zA);
-            if (ci_begin + 1 < ci_end) fetch(ci_begin + 1, dyB, zB);
-            if (tid == 0) CAC_TL(9);
-            stage(ci_begin, base0, dyA, zA);
-        }
+        fetch(ci_begin, true, dyA, zA); // (every workgroup has at least one chunk)
+        fetch(ci_begin + 1, ci_begin + 1 < ci_end, dyB, zB);
+        if (tid == 0) CAC_TL(9);
+        stage(ci_begin, base0, dyA, zA);
         if (tid == 0) CAC_TL(10);
         __syncthreads(); // buffer 0 holds the first chunk
         CAC_TA_DECL
         for (int ci = ci_begin; ci < ci_end; ci += 2) {
             // MFMA waves are on buffer 0 (chunk ci); set B holds chunk ci+1
-            if (ci + 2 < ci_end) fetch(ci + 2, dyA, zA);
+            fetch(ci + 2, ci + 2 < ci_end, dyA, zA);
             CAC_TA(0);
 #ifdef CAC_TIMELINE
             __builtin_amdgcn_s_waitcnt(0xF7C); // vmcnt(12): everything but the fetch just issued has arrived
@@ -381,7 +426,7 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
             CAC_TA(2);
             if (ci + 1 >= ci_end) break;
             // MFMA waves are on buffer 1 (chunk ci+1); set A holds chunk ci+2
-            if (ci + 3 < ci_end) fetch(ci + 3, dyB, zB);
+            fetch(ci + 3, ci + 3 < ci_end, dyB, zB);
             CAC_TA(0);
 #ifdef CAC_TIMELINE
             __builtin_amdgcn_s_waitcnt(0xF7C);
@@ -943,6 +988,7 @@ bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
     p.m_pr = magic_of(p.PR);
     p.m_zv = magic_of(p.ZV);
     p.m_nz = magic_of(p.NZ);
+    p.m_rb = magic_of(p.RB);
     // widest aligned vector for the global reads (tensor bases are 16-byte aligned)
     p.dy_vec = largest_vec(g.Q, 8);   // (informational: every read is a 16-byte load)
     p.z_vec = largest_vec(g.Wp, 8);
