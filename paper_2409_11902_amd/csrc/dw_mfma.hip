@@ -199,10 +199,18 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
     const int ot = tile / p.tiles_c, ct = tile - ot * p.tiles_c;
     const int o0 = ot * TILE_O, c0 = ct * TILE_C;
 
-    // Everything in LDS starts finite (zero): pad columns, the spare row of an odd
-    // chunk and the zero row are multiplied with something in every MFMA.
-    for (int i = threadIdx.x; i < p.lds_bytes / 16; i += 2 * NT) ((u32x4 *)smem)[i] = u32x4{0, 0, 0, 0};
-    __syncthreads();
+    // What is read without ever being staged must start as zero: the shared zero row and,
+    // in both buffers, the xhat part (every channel ends with an all-zero slot).  The row
+    // table and the dY part are rewritten in full for every chunk.
+    auto zero_fill = [&]() {
+        const uint32_t x_elems = TILE_C * p.x_cstride, x_off = rows_elems + TILE_O * p.dy_ostride;
+        u32x4 *l = (u32x4 *)smem;
+        for (uint32_t i = threadIdx.x; i < slot_w / 8; i += 2 * NT) l[i] = u32x4{0, 0, 0, 0};
+        for (uint32_t i = threadIdx.x; i < x_elems / 8; i += 2 * NT) {
+            l[(base0 + x_off) / 8 + i] = u32x4{0, 0, 0, 0};
+            l[(base1 + x_off) / 8 + i] = u32x4{0, 0, 0, 0};
+        }
+    };
 
     const int ci_begin = slice * p.chunks_per_slice;
     const int ci_end = min(ci_begin + p.chunks_per_slice, p.nchunks);
@@ -408,6 +416,8 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         fetch(ci_begin, true, dyA, zA); // (every workgroup has at least one chunk)
         fetch(ci_begin + 1, ci_begin + 1 < ci_end, dyB, zB);
         if (tid == 0) CAC_TL(9);
+        zero_fill(); // in the shadow of the first loads
+        __syncthreads();
         stage(ci_begin, base0, dyA, zA);
         if (tid == 0) CAC_TL(10);
         __syncthreads(); // buffer 0 holds the first chunk
@@ -445,6 +455,9 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
     // =============================== MFMA waves ===========================================
     const int tid = threadIdx.x, lane = tid & 63, wave = wave_id;
     const int wm = wave % WM, wn = (wave / WM) % WN, ks = wave / (WM * WN), half = lane >> 5, l32 = lane & 31;
+
+    zero_fill();
+    __syncthreads();
 
     f32x16 acc[MI][NI][T];
 #pragma unroll
@@ -499,14 +512,12 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
     // into `o`.  `tail`: the segment is the last of its row, nothing lies right of it.
     const uint32_t astep = 64 * p.dy_ostride, xstep = 64 * p.x_cstride, pw = 2 * p.PW;
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    auto request = [&](Ops &o, uint32_t ra, const uint32_t (&rx)[R], int seg, bool tail, const Ops *left = nullptr) {
+    // have_blk0: the caller has filled blk[0] already (the block a step looks at to its right is
+    // the next step's own block)
+    auto request = [&](Ops &o, uint32_t ra, const uint32_t (&rx)[R], int seg, bool tail, bool have_blk0 = false) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            // the block a step looks at to its right is the next step's own block
-            if (left && S > 1)
-                o.aw[mi].blk[0] = left->aw[mi].blk[1];
-            else
-                o.aw[mi].blk[0] = lds16(ra + mi * astep + 16 * seg);
+            if (!(have_blk0 && S > 1)) o.aw[mi].blk[0] = lds16(ra + mi * astep + 16 * seg);
             if constexpr (S > 1) // the dynamic LDS block starts with the zero row
                 o.aw[mi].blk[1] = lds16(tail ? lds0 : ra + mi * astep + 16 * seg + 16);
         }
@@ -543,25 +554,31 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
             // Row pairs as an outer loop, the SC segments of a row unrolled.  The operand sets
             // alternate from step to step; an odd SC swaps their roles from one row to the next.
             int rp = ks;
-#define CAC_ROW(A, B)                                                                               \
-    _Pragma("unroll") for (int sgi = 0; sgi < SC; ++sgi)                                            \
-    {                                                                                               \
-        Ops &use = (sgi & 1) ? B : A;                                                               \
-        Ops &get = (sgi & 1) ? A : B;                                                               \
-        if (sgi + 1 < SC) {                                                                         \
-            _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) get.aw[mi].prev3 = use.aw[mi].blk[0][3]; \
-            request(get, ra, rx, sgi + 1, sgi + 2 == SC, &use);                                     \
+            // step SGI of a row pair: MFMAs on USE while GET receives the operands of the next
+            // step (one segment to the right, or the first segment of the wave's next row pair)
+#define CAC_ROWSTEP(USE, GET, SGI)                                                                  \
+    if constexpr (SGI < SC) {                                                                       \
+        if constexpr (SGI + 1 < SC) {                                                               \
+            _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) {                                     \
+                GET.aw[mi].prev3 = USE.aw[mi].blk[0][3];                                            \
+                GET.aw[mi].blk[0] = USE.aw[mi].blk[1];                                              \
+            }                                                                                       \
+            request(GET, ra, rx, SGI + 1, SGI + 2 == SC, true);                                     \
         } else {                                                                                    \
             ra = ac + 2 * e_next[0];                                                                \
             _Pragma("unroll") for (int r = 0; r < R; ++r) rx[r] = xc + 2 * e_next[1 + r];           \
-            e_next = lds16(tab + 32 * min(rp + 2 * KS, nrp - 1));                 \
-            _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) get.aw[mi].prev3 = 0;                 \
-            request(get, ra, rx, 0, SC == 1);                                                       \
+            e_next = lds16(tab + 32 * min(rp + 2 * KS, nrp - 1));                                   \
+            _Pragma("unroll") for (int mi = 0; mi < MI; ++mi) GET.aw[mi].prev3 = 0;                 \
+            request(GET, ra, rx, 0, SC == 1);                                                       \
             rp += KS;                                                                               \
         }                                                                                           \
-        mfma_step(use);                                                                             \
+        mfma_step(USE);                                                                             \
         interleave();                                                                               \
     }
+#define CAC_ROW(A, B)                                                                              \
+    CAC_ROWSTEP(A, B, 0) CAC_ROWSTEP(B, A, 1) CAC_ROWSTEP(A, B, 2) CAC_ROWSTEP(B, A, 3)            \
+    CAC_ROWSTEP(A, B, 4) CAC_ROWSTEP(B, A, 5) CAC_ROWSTEP(A, B, 6) CAC_ROWSTEP(B, A, 7)
+            static_assert(SC <= 8, "row steps are written out up to 8");
             const int nrows = nsteps / SC;
             if constexpr (SC % 2 == 0) {
                 for (int i = 0; i < nrows; ++i) { CAC_ROW(X, Y) }
@@ -574,6 +591,7 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                 }
             }
 #undef CAC_ROW
+#undef CAC_ROWSTEP
             return;
         }
         int seg = 0, rp = ks;
@@ -1046,7 +1064,8 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
         }
     }
     if (!have_whole && !have_split) return false;
-    const bool use_split = have_split && (!have_whole || split.p.chunks_per_slice <= 12);
+    const int thr = g.R == 1 ? 12 : 48; // measured break-even (chunks per workgroup)
+    const bool use_split = have_split && (!have_whole || split.p.chunks_per_slice <= thr);
     *plan = use_split ? split : whole;
     return true;
 }
