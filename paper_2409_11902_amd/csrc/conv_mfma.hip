@@ -220,7 +220,7 @@ bool shape_gather(GatherParams &p, int *variant)
     const int wm = p.Mp <= 64 ? 1 : p.Mp <= 128 ? 2 : 4, wn = 4 / wm;
     const int px = p.Hc * p.Wc;
     // candidates (NI), largest pixel tile first; small maps take a smaller one
-    for (int ni : {4, 2, 1}) {
+    for (int ni : {2, 1}) { // (NI = 4 needs more than 256 registers: one wave per SIMD)
         const int pt = wn * ni * 32;
         if (ni > 1 && px <= pt / 2) continue;
         const int rows = min(p.Hc, (pt + p.Wc - 2) / p.Wc + 1); // class-grid rows a tile can touch

@@ -32,24 +32,9 @@
 // plus one shared all-zero row.  The inflated activation exists only here:
 // expanded horizontally when written to LDS, expanded vertically by mapping an
 // input row h to the slot of Z row h/kh.
-#include <stdlib.h>
 
 #include "common.h"
 #include "dw_mfma.h"
-
-#ifdef CAC_TIMELINE
-__device__ long long cac_timeline[1024 * 16];
-extern "C" int cac_timeline_read(long long *host) { return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(cac_timeline), sizeof(long long) * 1024 * 16); }
-#define CAC_TL(slot) do { if ((threadIdx.x & 63) == 0 && v < 1024) cac_timeline[v * 16 + (slot)] = wall_clock64(); } while (0)
-#define CAC_TA_DECL long long ta_t = wall_clock64(), ta_acc[4] = {0, 0, 0, 0};
-#define CAC_TA(k) do { long long n_ = wall_clock64(); ta_acc[k] += n_ - ta_t; ta_t = n_; } while (0)
-#define CAC_TA_OUT(base) do { if ((threadIdx.x & 63) == 0 && v < 1024) { cac_timeline[v * 16 + (base)] = ta_acc[0]; cac_timeline[v * 16 + (base) + 1] = ta_acc[1]; cac_timeline[v * 16 + (base) + 2] = ta_acc[2]; if ((base) == 11) cac_timeline[v * 16 + 7] = ta_acc[3]; } } while (0)
-#else
-#define CAC_TL(slot) do {} while (0)
-#define CAC_TA_DECL
-#define CAC_TA(k) do {} while (0)
-#define CAC_TA_OUT(base) do {} while (0)
-#endif
 
 namespace cac {
 
@@ -193,7 +178,6 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
     const int per_xcd = gridDim.x >> 3;
     const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (v >= p.total_wg) return;
-    if (threadIdx.x == 0) CAC_TL(0);
     const int ntiles = p.tiles_o * p.tiles_c;
     const int slice = v / ntiles, tile = v - slice * ntiles;
     const int ot = tile / p.tiles_c, ct = tile - ot * p.tiles_c;
@@ -412,42 +396,23 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         };
 
         u32x4 dyA[kMaxDy], zA[kMaxZ], dyB[kMaxDy], zB[kMaxZ];
-        if (tid == 0) CAC_TL(8);
         fetch(ci_begin, true, dyA, zA); // (every workgroup has at least one chunk)
         fetch(ci_begin + 1, ci_begin + 1 < ci_end, dyB, zB);
-        if (tid == 0) CAC_TL(9);
         zero_fill(); // in the shadow of the first loads
         __syncthreads();
         stage(ci_begin, base0, dyA, zA);
-        if (tid == 0) CAC_TL(10);
         __syncthreads(); // buffer 0 holds the first chunk
-        CAC_TA_DECL
         for (int ci = ci_begin; ci < ci_end; ci += 2) {
             // MFMA waves are on buffer 0 (chunk ci); set B holds chunk ci+1
             fetch(ci + 2, ci + 2 < ci_end, dyA, zA);
-            CAC_TA(0);
-#ifdef CAC_TIMELINE
-            __builtin_amdgcn_s_waitcnt(0xF7C); // vmcnt(12): everything but the fetch just issued has arrived
-            CAC_TA(3);
-#endif
             if (ci + 1 < ci_end) stage(ci + 1, base1, dyB, zB);
-            CAC_TA(1);
             __syncthreads();
-            CAC_TA(2);
             if (ci + 1 >= ci_end) break;
             // MFMA waves are on buffer 1 (chunk ci+1); set A holds chunk ci+2
             fetch(ci + 3, ci + 3 < ci_end, dyB, zB);
-            CAC_TA(0);
-#ifdef CAC_TIMELINE
-            __builtin_amdgcn_s_waitcnt(0xF7C);
-            CAC_TA(3);
-#endif
             if (ci + 2 < ci_end) stage(ci + 2, base0, dyA, zA);
-            CAC_TA(1);
             __syncthreads();
-            CAC_TA(2);
         }
-        if (tid == 0) CAC_TA_OUT(11);
         if constexpr (KS > 1) __syncthreads(); // the barrier inside the MFMA waves' cross-wave sum
         return;
     }
@@ -651,25 +616,14 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
 #undef CAC_STEP
     };
 
-    if (tid == 0) CAC_TL(1);
     __syncthreads(); // buffer 0 holds the first chunk
-    if (tid == 0) CAC_TL(2);
-    CAC_TA_DECL
     for (int ci = ci_begin; ci < ci_end; ci += 2) {
         compute(base0);
-        CAC_TA(0);
-        if (tid == 0 && ci == ci_begin) CAC_TL(3);
         __syncthreads();
-        CAC_TA(1);
-        if (tid == 0 && ci == ci_begin) CAC_TL(4);
         if (ci + 1 >= ci_end) break;
         compute(base1);
-        CAC_TA(0);
         __syncthreads();
-        CAC_TA(1);
     }
-    if (tid == 0) CAC_TL(5);
-    if (tid == 0) CAC_TA_OUT(14);
 
     // ---- epilogue --------------------------------------------------------------------
     // accumulator register j of lane l holds row 8*(j/4) + 4*(l/32) + j%4, column l%32.
@@ -742,7 +696,6 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                 }
             }
 #undef CAC_GROUP
-    if (tid == 0) CAC_TL(6);
 }
 
 // Sums the slices' partial tiles in slice order and writes dW in its own layout.
