@@ -57,16 +57,22 @@ __global__ void __launch_bounds__(256) nchw_to_nhwc_kernel(const bf16_t *__restr
     }
 }
 
-// W [O][C][R][S] -> Wt [R*S][Mp][KCp]; forward: m = o, kc = c; data gradient: m = c, kc = o.
+// W [O][C][R][S] -> Wt in MFMA fragment order [R*S][KCp/16][Mp/32][lane 64][8]: lane l of a wave
+// holds row m = 32*mblk + l%32 and the 8 channels kc = 16*kblk + 8*(l/32) ..., so a wave reads the
+// A fragment of a (tap, 16-channel block, 32-row block) as one contiguous KiB.
+// Forward: m = o, kc = c; data gradient: m = c, kc = o.
 __global__ void __launch_bounds__(256) filter_repack_kernel(const bf16_t *__restrict__ W, bf16_t *__restrict__ Wt, int O, int C,
                                                             int RS, int Mp, int KCp, int transpose)
 {
     const long total = (long)RS * Mp * KCp;
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
-    const int kc = idx % KCp;
-    const long t1 = idx / KCp;
-    const int m = t1 % Mp, tap = t1 / Mp;
+    const int e = idx & 7, lane = (idx >> 3) & 63;
+    long rest = idx >> 9;
+    const int mblk = rest % (Mp / 32);
+    rest /= Mp / 32;
+    const int kblk = rest % (KCp / 16), tap = rest / (KCp / 16);
+    const int m = mblk * 32 + (lane & 31), kc = kblk * 16 + 8 * (lane >> 5) + e;
     const int o = transpose ? kc : m, c = transpose ? m : kc;
     Wt[idx] = (o < O && c < C) ? W[((long)o * C + c) * RS + tap] : (bf16_t)0;
 }
@@ -125,8 +131,9 @@ __global__ void __launch_bounds__(256) conv_gather_kernel(GatherParams p)
     const bool wave_live = m0 < p.Mp; // waves past the (padded) output channels only help staging
 
     // filter fragment of (tap t, channel block kk of 16) for output channel block mi
+    const uint32_t kblks = p.KCp / 16, mblks = p.Mp / 32;
     auto wfrag = [&](int t, int kc0, int mi) {
-        const uint32_t e = ((uint32_t)(p.wtap[t] * p.Mp + m0 + mi * 32 + l32) * p.KCp + kc0 + 8 * half) * 2u;
+        const uint32_t e = (((uint32_t)(p.wtap[t] * kblks + (kc0 >> 4)) * mblks + (m0 >> 5) + mi) * 64 + lane) * 16u;
         return __builtin_amdgcn_raw_buffer_load_b128(rs_w, wave_live ? e : kNoLoad, 0, 0);
     };
 
@@ -143,16 +150,19 @@ __global__ void __launch_bounds__(256) conv_gather_kernel(GatherParams p)
         }
         __syncthreads();
         if (!wave_live) continue;
-        // ---- taps x 16-channel blocks, filter fragments one step ahead
+        // ---- taps x 16-channel blocks, filter fragments two steps ahead
         const int nsteps = p.ntaps * (KC / 16);
-        u32x4 wcur[MI], wnxt[MI];
+        u32x4 wcur[MI], wnxt[MI], wnn[MI];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) wcur[mi] = wfrag(0, kcb, mi);
+        for (int mi = 0; mi < MI; ++mi) {
+            wcur[mi] = wfrag(0, kcb, mi);
+            wnxt[mi] = wfrag(min(1, nsteps - 1) / (KC / 16), kcb + (min(1, nsteps - 1) % (KC / 16)) * 16, mi);
+        }
         for (int st = 0; st < nsteps; ++st) {
             const int t = st / (KC / 16), kk = st - t * (KC / 16);
-            const int st1 = min(st + 1, nsteps - 1), t1 = st1 / (KC / 16), kk1 = st1 - t1 * (KC / 16);
+            const int st2 = min(st + 2, nsteps - 1), t2 = st2 / (KC / 16), kk2 = st2 - t2 * (KC / 16);
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) wnxt[mi] = wfrag(t1, kcb + kk1 * 16, mi);
+            for (int mi = 0; mi < MI; ++mi) wnn[mi] = wfrag(t2, kcb + kk2 * 16, mi);
             const uint32_t toff = (uint32_t)(((p.dh[t] - p.dhmin) * p.PWd + (p.dw[t] - p.dwmin)) * KCS + kk * 16 + 8 * half) * 2u;
             u32x4 b[NI];
 #pragma unroll
@@ -167,7 +177,10 @@ __global__ void __launch_bounds__(256) conv_gather_kernel(GatherParams p)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[mi][ni], 0, 0, 0);
                 }
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) wcur[mi] = wnxt[mi];
+            for (int mi = 0; mi < MI; ++mi) {
+                wcur[mi] = wnxt[mi];
+                wnxt[mi] = wnn[mi];
+            }
         }
     }
     if (!wave_live) return;
