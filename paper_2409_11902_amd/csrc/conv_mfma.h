@@ -6,7 +6,7 @@ namespace cac {
 
 struct GatherParams {
     const bf16_t *in;   // [N][Hin][Win][KCp], channels last
-    const bf16_t *wt;   // [ntaps_total][Mp][KCp]
+    const bf16_t *wt;   // [ntaps_total][KCp/16][Mp/32][64][8], MFMA fragment order
     const bf16_t *bias; // [M] or null
     bf16_t *out;        // [N][M][Hout][Wout]
     int N, M, Mp, KCp;
@@ -16,7 +16,10 @@ struct GatherParams {
     int ntaps, ntaps_total;
     int dh[9], dw[9], wtap[9];
     int dhmin, dwmin;
-    int PH, PWd;        // input patch staged per workgroup (rows, columns)
+    int PH, PWd;        // input patch of one image staged per workgroup (rows, columns)
+    int IPT, patch_px;  // images per pixel tile; patch pixels of the whole tile
+    int tiles_per_img, ngrp, gpw, nkb; // tiles per image; image groups; groups per workgroup; channel blocks
+    uint32_t m_wc, m_ppi, m_pwd, m_nkb, m_img; // division magics of Wc, Hc*Wc, PWd, nkb, PH*PWd
 };
 
 size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad);

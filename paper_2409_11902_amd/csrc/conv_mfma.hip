@@ -84,38 +84,119 @@ __global__ void __launch_bounds__(256) zero_fill_kernel(u32x4 *dst, long n16)
 }
 
 // ---- the gather GEMM ----------------------------------------------------------------
+//
+// Workgroup: 4 MFMA waves (WM x WN, a wave owns 64 (m) x 32*NI (pixels)) and 4 copy waves.
+// A pixel tile is PT = WN*NI*32 pixels of one image, or IPT whole images when an image has at
+// most PT/2 pixels.  The work of a workgroup is a run of "units" (the same tile position in
+// consecutive image groups), each unit nkb "stages" of KC input channels; the stages of the
+// whole run form one software pipeline: the copy waves keep two stages of global loads in
+// flight and write the patch of stage s+1 into the LDS buffer the MFMA waves are not reading
+// (one barrier per stage).  Filter fragments come straight from global memory (fragment order,
+// cache resident), fetched two steps ahead by the MFMA waves, whose only other memory traffic
+// is LDS reads, so their load counter never waits on the long-latency patch loads.
+constexpr int kMaxItems = 12; // 16-byte patch items a copy thread moves per stage
+// floor(x / d) for small x (x * d < 2^32) with magic = ceil(2^32 / d), 0 standing for d = 1
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t magic) { return magic ? __umulhi(x, magic) : x; }
+constexpr uint32_t kNoElem = 0x40000000u;
 
 template <int NI, int WM, int WN>
-__global__ void __launch_bounds__(256) conv_gather_kernel(GatherParams p)
+__global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 {
     constexpr int MI = 2;
-    constexpr int PT = WN * NI * 32; // pixels per workgroup
+    constexpr int PT = WN * NI * 32; // pixel lanes per workgroup
     extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t *patch = (bf16_t *)smem;
+    const uint32_t buf_bytes = (uint32_t)p.patch_px * KCS * 2;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave % WM, wn = wave / WM, half = lane >> 5, l32 = lane & 31;
-    const int tiles_per_img = (p.Hc * p.Wc + PT - 1) / PT;
-    const int n = blockIdx.x / tiles_per_img, tile = blockIdx.x - n * tiles_per_img;
-    const int pix0 = tile * PT;                    // first class-grid pixel of the tile
-    const int i0 = pix0 / p.Wc;                    // its row
-    const int m0 = (blockIdx.y * WM + wm) * 64;    // this wave's first output channel
-
+    const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tau = blockIdx.x % p.tiles_per_img, run = blockIdx.x / p.tiles_per_img;
+    const int g_begin = run * p.gpw, g_end = min(g_begin + p.gpw, p.ngrp);
+    const int nstages = (g_end - g_begin) * p.nkb;
+    const int ppi = p.Hc * p.Wc;
+    const int pix0 = p.IPT > 1 ? 0 : tau * PT;      // first class-grid pixel of the tile
+    const int i0 = fdiv(pix0, p.m_wc);               // its row
     // input patch: rows i0*is + dhmin ..., all columns dwmin ... (Wc-1)*is + dwmax
     const int hin0 = i0 * p.is + p.dhmin, win0 = p.dwmin;
-    const int patch_px = p.PH * p.PWd;
 
-    // this lane's pixels: LDS byte offset of their tap-(dhmin,dwmin) input pixel; class-grid coordinates
+    if (wave_id >= 4) {
+        // =========================== copy waves ===========================================
+        const int tid = threadIdx.x - 256;
+        const int items = p.patch_px * (KC / 8);
+        const int v8 = (tid & 3) * 8;               // channel offset of this lane's items in the stage
+        uint32_t eq[kMaxItems], gq[kMaxItems], lq[kMaxItems];
+#pragma unroll
+        for (int q = 0; q < kMaxItems; ++q) {
+            const int it = tid + 256 * q;
+            const int pp = it >> 2;
+            const int g = fdiv(pp, p.m_img), rem = pp - g * (p.PH * p.PWd);
+            const int pr = fdiv(rem, p.m_pwd), pc = rem - pr * p.PWd;
+            const int hin = hin0 + pr, win = win0 + pc;
+            const bool ok = it < items && hin >= 0 && hin < p.Hin && win >= 0 && win < p.Win;
+            eq[q] = ok ? (uint32_t)((g * p.Hin + hin) * p.Win + win) * p.KCp + v8 : kNoElem;
+            gq[q] = g;
+            lq[q] = it < items ? (uint32_t)(pp * KCS + v8) * 2u : 0xffffffffu;
+        }
+        const rsrc_t rs_in = make_rsrc(p.in, (uint32_t)p.N * p.Hin * p.Win * p.KCp * 2u);
+        // global -> registers for stage s (dead stages load nothing but are issued all the same:
+        // the number of loads in flight is then the same on every path)
+        auto fetch = [&](int s, u32x4 (&r)[kMaxItems]) {
+            const int u = fdiv(s, p.m_nkb), kb = s - u * p.nkb;
+            const int n_base = (g_begin + u) * p.IPT;
+            const uint32_t sbase = (uint32_t)n_base * p.Hin * p.Win * p.KCp + kb * KC;
+            const bool lane_ok = s < nstages && kb * KC + v8 < p.KCp;
+            const uint32_t lim = lane_ok ? (uint32_t)max(p.N - n_base, 0) : 0u;
+#pragma unroll
+            for (int q = 0; q < kMaxItems; ++q) {
+                const uint32_t e = gq[q] < lim ? eq[q] + sbase : kNoElem;
+                r[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_in, e * 2u, 0, 0);
+            }
+        };
+        auto put = [&](uint32_t buf, const u32x4 (&r)[kMaxItems]) {
+#pragma unroll
+            for (int q = 0; q < kMaxItems; ++q)
+                if (lq[q] != 0xffffffffu) *(u32x4 *)(smem + buf + lq[q]) = r[q];
+        };
+        u32x4 ra[kMaxItems], rb[kMaxItems];
+        fetch(0, ra);
+        fetch(1, rb);
+        put(0, ra);
+        __syncthreads();
+        for (int s = 0; s < nstages; s += 2) {
+            fetch(s + 2, ra);
+            if (s + 1 < nstages) put(buf_bytes, rb);
+            __syncthreads();
+            if (s + 1 >= nstages) break;
+            fetch(s + 3, rb);
+            if (s + 2 < nstages) put(0, ra);
+            __syncthreads();
+        }
+        return;
+    }
+
+    // =============================== MFMA waves ===========================================
+    const int tid = threadIdx.x, lane = tid & 63, wave = wave_id;
+    const int wm = wave % WM, wn = wave / WM, half = lane >> 5, l32 = lane & 31;
+    const int m0 = (blockIdx.y * WM + wm) * 64;    // this wave's first output channel
+    const bool wave_live = m0 < p.Mp;              // waves past the (padded) output channels only keep the barriers
+
+    // this lane's pixels: image within the tile, class-grid coordinates, LDS byte offset of their
+    // tap-(dhmin,dwmin) input pixel
     uint32_t pbase[NI];
-    int pi[NI], pj[NI];
+    int pi[NI], pj[NI], pg[NI];
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-        const int px = pix0 + (wn * NI + ni) * 32 + l32;
-        const bool ok = px < p.Hc * p.Wc;
-        const int i = px / p.Wc, j = px - i * p.Wc;
+        const int idx = (wn * NI + ni) * 32 + l32;
+        int g = 0, px = pix0 + idx;
+        bool ok = px < ppi;
+        if (p.IPT > 1) {
+            g = fdiv(idx, p.m_ppi);
+            px = idx - g * ppi;
+            ok = g < p.IPT;
+        }
+        const int i = fdiv(px, p.m_wc), j = px - i * p.Wc;
         pi[ni] = ok ? i : -1;
         pj[ni] = j;
-        pbase[ni] = ok ? (uint32_t)(((i - i0) * p.is * p.PWd + j * p.is) * KCS * 2) : 0u;
+        pg[ni] = g;
+        pbase[ni] = ok ? (uint32_t)(((g * p.PH + (i - i0) * p.is) * p.PWd + j * p.is) * KCS * 2) : 0u;
     }
 
     f32x16 acc[MI][NI];
@@ -126,80 +207,111 @@ __global__ void __launch_bounds__(256) conv_gather_kernel(GatherParams p)
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.f;
 
-    const rsrc_t rs_in = make_rsrc(p.in, (uint32_t)p.N * p.Hin * p.Win * p.KCp * 2u);
     const rsrc_t rs_w = make_rsrc(p.wt, (uint32_t)p.ntaps_total * p.Mp * p.KCp * 2u);
-    const bool wave_live = m0 < p.Mp; // waves past the (padded) output channels only help staging
-
-    // filter fragment of (tap t, channel block kk of 16) for output channel block mi
     const uint32_t kblks = p.KCp / 16, mblks = p.Mp / 32;
-    auto wfrag = [&](int t, int kc0, int mi) {
-        const uint32_t e = (((uint32_t)(p.wtap[t] * kblks + (kc0 >> 4)) * mblks + (m0 >> 5) + mi) * 64 + lane) * 16u;
-        return __builtin_amdgcn_raw_buffer_load_b128(rs_w, wave_live ? e : kNoLoad, 0, 0);
-    };
-
-    for (int kcb = 0; kcb < p.KCp; kcb += KC) {
-        // ---- stage the patch: KC channels of every patch pixel, zeros outside the image
-        __syncthreads();
-        for (int it = tid; it < patch_px * (KC / 8); it += 256) {
-            const int pp = it / (KC / 8), v = it - pp * (KC / 8);
-            const int pr = pp / p.PWd, pc = pp - pr * p.PWd;
-            const int hin = hin0 + pr, win = win0 + pc;
-            const bool ok = hin >= 0 && hin < p.Hin && win >= 0 && win < p.Win && kcb + v * 8 < p.KCp;
-            const uint32_t e = (((uint32_t)(n * p.Hin + hin) * p.Win + win) * p.KCp + kcb + v * 8) * 2u;
-            *(u32x4 *)(patch + pp * KCS + v * 8) = __builtin_amdgcn_raw_buffer_load_b128(rs_in, ok ? e : kNoLoad, 0, 0);
-        }
-        __syncthreads();
-        if (!wave_live) continue;
-        // ---- taps x 16-channel blocks, filter fragments two steps ahead
-        const int nsteps = p.ntaps * (KC / 16);
-        u32x4 wcur[MI], wnxt[MI], wnn[MI];
+    // Per-tap constants in vector registers (uniform values; with constant indices after
+    // unrolling they never have to be reloaded inside the loop): byte offset of the tap's
+    // filter fragments and LDS byte offset of the tap within the patch (with this half-wave's
+    // 8 channels).
+    constexpr uint32_t kFrag = 64 * 16; // bytes of one fragment of the repacked filter
+    uint32_t wofs[9], toff[9];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            wcur[mi] = wfrag(0, kcb, mi);
-            wnxt[mi] = wfrag(min(1, nsteps - 1) / (KC / 16), kcb + (min(1, nsteps - 1) % (KC / 16)) * 16, mi);
-        }
-        for (int st = 0; st < nsteps; ++st) {
-            const int t = st / (KC / 16), kk = st - t * (KC / 16);
-            const int st2 = min(st + 2, nsteps - 1), t2 = st2 / (KC / 16), kk2 = st2 - t2 * (KC / 16);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) wnn[mi] = wfrag(t2, kcb + kk2 * 16, mi);
-            const uint32_t toff = (uint32_t)(((p.dh[t] - p.dhmin) * p.PWd + (p.dw[t] - p.dwmin)) * KCS + kk * 16 + 8 * half) * 2u;
-            u32x4 b[NI];
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) b[ni] = *(const u32x4 *)(smem + pbase[ni] + toff);
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    union { u32x4 u; bf16x8 v; } af, bf;
-                    af.u = wcur[mi];
-                    bf.u = b[ni];
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[mi][ni], 0, 0, 0);
-                }
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                wcur[mi] = wnxt[mi];
-                wnxt[mi] = wnn[mi];
-            }
-        }
+    for (int t = 0; t < 9; ++t) {
+        wofs[t] = (uint32_t)p.wtap[t] * kblks * mblks * kFrag;
+        toff[t] = (uint32_t)(((p.dh[t] - p.dhmin) * p.PWd + (p.dw[t] - p.dwmin)) * KCS + 8 * half) * 2u;
     }
-    if (!wave_live) return;
+    // this lane's part of a fragment address; a dead wave reads nothing
+    const uint32_t wlane = wave_live ? (uint32_t)(m0 >> 5) * kFrag + lane * 16u : kNoLoad;
+    // filter fragment of (tap offset wo, 16-channel block kblk) for output channel block mi
+    auto wfrag = [&](uint32_t wo, int kblk, int mi) {
+        return __builtin_amdgcn_raw_buffer_load_b128(rs_w, wlane + wo + (uint32_t)(kblk * mblks + mi) * kFrag, 0, 0);
+    };
+    // Fragments are fetched two steps ahead: a tap is KC/16 = 2 steps, so while step (t, kk) runs,
+    // the fragment of (t+1, kk) -- or of the next stage's first tap -- is requested.  The pixel
+    // operands (LDS) are requested one step ahead.
+    static_assert(KC / 16 == 2, "the prefetch distance below is one tap");
+    u32x4 wcur[MI], wnxt[MI], wnn[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        wcur[mi] = wfrag(wofs[0], 0, mi);
+        wnxt[mi] = wfrag(wofs[0], 1, mi);
+    }
 
-    // ---- epilogue: bias, bfloat16, NCHW.  Register j of lane l: row 8*(j/4) + 4*(l/32) + j%4, column l%32.
+    __syncthreads(); // buffer 0 holds stage 0
+    int kb = 0, unit = 0;
+    for (int s = 0; s < nstages; ++s) {
+        if (wave_live) {
+            const uint32_t buf = (s & 1) ? buf_bytes : 0u;
+            const int kb_next = kb + 1 == p.nkb ? 0 : kb + 1;
+            u32x4 bcur[NI], bnxt[NI];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+            for (int ni = 0; ni < NI; ++ni) bcur[ni] = *(const u32x4 *)(smem + buf + pbase[ni] + toff[0]);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int m = m0 + mi * 32 + 8 * (j / 4) + 4 * half + (j % 4);
-            if (m >= p.M) continue;
-            const float bias = p.bias ? bf16_to_f32(p.bias[m]) : 0.f;
+            for (int t = 0; t < 9; ++t) {
+                if (t >= p.ntaps) break;
+                const bool last = t + 1 >= p.ntaps;
+                const uint32_t wo_n = last ? wofs[0] : wofs[t + 1 < 9 ? t + 1 : 0];
+                const uint32_t to_n = toff[t + 1 < 9 ? t + 1 : 0];
+                const int kblk_n = (last ? kb_next : kb) * (KC / 16);
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                if (pi[ni] < 0) continue;
-                const int h = pi[ni] * p.os + p.a0, w = pj[ni] * p.os + p.b0;
-                p.out[(((long)n * p.M + m) * p.Hout + h) * p.Wout + w] = f32_to_bf16(acc[mi][ni][j] + bias);
+                for (int kk = 0; kk < KC / 16; ++kk) {
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) wnn[mi] = wfrag(wo_n, kblk_n + kk, mi);
+                    // next step's pixels: the second channel half of this tap, or the next tap
+                    // (nothing after the stage's last step: the other buffer is not ready yet)
+                    if (kk == 0) {
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) bnxt[ni] = *(const u32x4 *)(smem + buf + pbase[ni] + toff[t] + 32);
+                    } else if (!last) {
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) bnxt[ni] = *(const u32x4 *)(smem + buf + pbase[ni] + to_n);
+                    }
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int mi = 0; mi < MI; ++mi) {
+                            union { u32x4 u; bf16x8 v; } af, bf;
+                            af.u = wcur[mi];
+                            bf.u = bcur[ni];
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[mi][ni], 0, 0, 0);
+                        }
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) {
+                        wcur[mi] = wnxt[mi];
+                        wnxt[mi] = wnn[mi];
+                    }
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) bcur[ni] = bnxt[ni];
+                }
+            }
+            if (kb == p.nkb - 1) {
+                // ---- epilogue of the unit: bias, bfloat16, NCHW.  Register j of lane l: row
+                // 8*(j/4) + 4*(l/32) + j%4, column l%32.
+                const int n_base = (g_begin + unit) * p.IPT;
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int m = m0 + mi * 32 + 8 * (j / 4) + 4 * half + (j % 4);
+                        const float bias = (p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) {
+                            const int n = n_base + pg[ni];
+                            if (m < p.M && pi[ni] >= 0 && n < p.N) {
+                                const int h = pi[ni] * p.os + p.a0, w = pj[ni] * p.os + p.b0;
+                                p.out[(((long)n * p.M + m) * p.Hout + h) * p.Wout + w] = f32_to_bf16(acc[mi][ni][j] + bias);
+                            }
+                            acc[mi][ni][j] = 0.f;
+                        }
+                    }
             }
         }
+        if (++kb == p.nkb) {
+            kb = 0;
+            ++unit;
+        }
+        __syncthreads();
+    }
 }
 
 template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p, hipStream_t st)
@@ -211,16 +323,15 @@ template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    constexpr int PT = WN * NI * 32;
-    const int tiles_per_img = (p.Hc * p.Wc + PT - 1) / PT;
-    dim3 grid(tiles_per_img * p.N, (p.Mp / 64 + WM - 1) / WM);
-    hipLaunchKernelGGL(kern, grid, dim3(256), (size_t)p.PH * p.PWd * KCS * 2, st, p);
+    const int runs = (p.ngrp + p.gpw - 1) / p.gpw;
+    dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM);
+    hipLaunchKernelGGL(kern, grid, dim3(512), (size_t)2 * p.patch_px * KCS * 2, st, p);
     return hipGetLastError();
 }
 
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
-// Chooses the workgroup shape and fills the patch extents; false if no shape fits LDS.
+// Chooses the workgroup shape and fills the tiling; false if no shape fits.
 bool shape_gather(GatherParams &p, int *variant)
 {
     p.dhmin = p.dwmin = 1 << 30;
@@ -230,32 +341,62 @@ bool shape_gather(GatherParams &p, int *variant)
         p.dwmin = min(p.dwmin, p.dw[t]); dwmax = max(dwmax, p.dw[t]);
     }
     p.PWd = (p.Wc - 1) * p.is + (dwmax - p.dwmin) + 1;
-    const int wm = p.Mp <= 64 ? 1 : p.Mp <= 128 ? 2 : 4, wn = 4 / wm;
-    const int px = p.Hc * p.Wc;
-    // candidates (NI), largest pixel tile first; small maps take a smaller one
-    for (int ni : {2, 1}) { // (NI = 4 needs more than 256 registers: one wave per SIMD)
-        const int pt = wn * ni * 32;
-        if (ni > 1 && px <= pt / 2) continue;
-        const int rows = min(p.Hc, (pt + p.Wc - 2) / p.Wc + 1); // class-grid rows a tile can touch
-        p.PH = (rows - 1) * p.is + (dhmax - p.dhmin) + 1;
-        if ((long)p.PH * p.PWd * KCS * 2 > 150 * 1024) continue;
-        *variant = (ni == 4 ? 0 : ni == 2 ? 3 : 6) + (wm == 1 ? 0 : wm == 2 ? 1 : 2);
-        return true;
+    p.nkb = (p.KCp + KC - 1) / KC;
+    const int ppi = p.Hc * p.Wc;
+    auto magic = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
+    p.m_wc = magic(p.Wc); p.m_ppi = magic(ppi); p.m_pwd = magic(p.PWd); p.m_nkb = magic(p.nkb);
+    // Candidates: waves along m (wm) x pixel blocks per wave (ni), large tiles first; the first
+    // that fills the chip is taken, else the one with the most workgroups.
+    GatherParams best{};
+    long best_wgs = -1;
+    int best_variant = 0;
+    for (int wm : {4, 2, 1}) {
+        if (wm * 64 > p.Mp && wm > 1) continue;
+        const int wn = 4 / wm;
+        for (int ni : {2, 1}) {
+            GatherParams q = p;
+            const int pt = wn * ni * 32;
+            q.IPT = 2 * ppi <= pt ? pt / ppi : 1;
+            if (q.IPT > 1) {
+                q.tiles_per_img = 1;
+                q.PH = (q.Hc - 1) * q.is + (dhmax - q.dhmin) + 1;
+            } else {
+                q.tiles_per_img = (ppi + pt - 1) / pt;
+                const int rows = min(q.Hc, (pt + q.Wc - 2) / q.Wc + 1); // class-grid rows a tile can touch
+                q.PH = (rows - 1) * q.is + (dhmax - q.dhmin) + 1;
+            }
+            q.patch_px = q.IPT * q.PH * q.PWd;
+            if (q.patch_px * (KC / 8) > 256 * kMaxItems) continue;
+            if ((long)2 * q.patch_px * KCS * 2 > 150 * 1024) continue;
+            q.m_img = magic(q.PH * q.PWd);
+            q.ngrp = (q.N + q.IPT - 1) / q.IPT;
+            const long wgs1 = (long)q.tiles_per_img * q.ngrp * ((q.Mp / 64 + wm - 1) / wm);
+            // a few units per workgroup (a longer pipeline) as long as every CU still gets a workgroup
+            q.gpw = (int)max(1L, min((long)((8 + q.nkb - 1) / q.nkb), wgs1 / 256));
+            const long wgs = (long)q.tiles_per_img * ((q.ngrp + q.gpw - 1) / q.gpw) * ((q.Mp / 64 + wm - 1) / wm);
+            const int v = (ni == 2 ? 0 : 3) + (wm == 1 ? 0 : wm == 2 ? 1 : 2);
+            if (wgs >= 256) {
+                p = q;
+                *variant = v;
+                return true;
+            }
+            if (wgs > best_wgs) { best_wgs = wgs; best = q; best_variant = v; }
+        }
     }
-    return false;
+    if (best_wgs < 0) return false;
+    p = best;
+    *variant = best_variant;
+    return true;
 }
 
 hipError_t run_gather(const GatherParams &p, int variant, hipStream_t st)
 {
     switch (variant) {
-    case 0: return launch_gather<4, 1, 4>(p, st);
-    case 1: return launch_gather<4, 2, 2>(p, st);
-    case 2: return launch_gather<4, 4, 1>(p, st);
-    case 3: return launch_gather<2, 1, 4>(p, st);
-    case 4: return launch_gather<2, 2, 2>(p, st);
-    case 5: return launch_gather<2, 4, 1>(p, st);
-    case 6: return launch_gather<1, 1, 4>(p, st);
-    case 7: return launch_gather<1, 2, 2>(p, st);
+    case 0: return launch_gather<2, 1, 4>(p, st);
+    case 1: return launch_gather<2, 2, 2>(p, st);
+    case 2: return launch_gather<2, 4, 1>(p, st);
+    case 3: return launch_gather<1, 1, 4>(p, st);
+    case 4: return launch_gather<1, 2, 2>(p, st);
     default: return launch_gather<1, 4, 1>(p, st);
     }
 }
