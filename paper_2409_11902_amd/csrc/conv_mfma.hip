@@ -99,7 +99,10 @@ constexpr int kMaxItems = 12; // 16-byte patch items a copy thread moves per sta
 __device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t magic) { return magic ? __umulhi(x, magic) : x; }
 constexpr uint32_t kNoElem = 0x40000000u;
 
-template <int NI, int WM, int WN>
+// TR: the accumulators hold the transposed tile (lanes = output channels, registers = pixels):
+// a lane then owns runs of 4 consecutive pixels and writes them as one 8-byte store.  Used when
+// consecutive pixels of the launch are consecutive and 8-byte aligned in memory.
+template <int NI, int WM, int WN, bool TR>
 __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 {
     constexpr int MI = 2;
@@ -273,7 +276,8 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                             union { u32x4 u; bf16x8 v; } af, bf;
                             af.u = wcur[mi];
                             bf.u = bcur[ni];
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[mi][ni], 0, 0, 0);
+                            acc[mi][ni] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf.v, af.v, acc[mi][ni], 0, 0, 0)
+                                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[mi][ni], 0, 0, 0);
                         }
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi) {
@@ -285,25 +289,61 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                 }
             }
             if (kb == p.nkb - 1) {
-                // ---- epilogue of the unit: bias, bfloat16, NCHW.  Register j of lane l: row
-                // 8*(j/4) + 4*(l/32) + j%4, column l%32.
+                // ---- epilogue of the unit: bias, bfloat16, NCHW
                 const int n_base = (g_begin + unit) * p.IPT;
+                if constexpr (TR) {
+                    // register j of lane l: pixel 8*(j/4) + 4*(l/32) + j%4 of the block, channel l%32
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int m = m0 + mi * 32 + 8 * (j / 4) + 4 * half + (j % 4);
+                    for (int mi = 0; mi < MI; ++mi) {
+                        const int m = m0 + mi * 32 + l32;
                         const float bias = (p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
 #pragma unroll
-                        for (int ni = 0; ni < NI; ++ni) {
-                            const int n = n_base + pg[ni];
-                            if (m < p.M && pi[ni] >= 0 && n < p.N) {
-                                const int h = pi[ni] * p.os + p.a0, w = pj[ni] * p.os + p.b0;
-                                p.out[(((long)n * p.M + m) * p.Hout + h) * p.Wout + w] = f32_to_bf16(acc[mi][ni][j] + bias);
+                        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                            for (int jq = 0; jq < 4; ++jq) {
+                                // the 4 pixels idx .. idx+3 of the tile (same image: an image's pixel
+                                // count is a multiple of 4 on this path)
+                                const int idx = (wn * NI + ni) * 32 + 8 * jq + 4 * half;
+                                int g = 0, px = pix0 + idx;
+                                if (p.IPT > 1) {
+                                    g = fdiv(idx, p.m_ppi);
+                                    px = idx - g * ppi;
+                                }
+                                const int n = n_base + g;
+                                if (m < p.M && px < ppi && g < p.IPT && n < p.N) {
+                                    const f32x16 &a = acc[mi][ni];
+                                    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+                                    const u32x2 v = {(uint32_t)f32_to_bf16(a[4 * jq] + bias) | ((uint32_t)f32_to_bf16(a[4 * jq + 1] + bias) << 16),
+                                                     (uint32_t)f32_to_bf16(a[4 * jq + 2] + bias) | ((uint32_t)f32_to_bf16(a[4 * jq + 3] + bias) << 16)};
+                                    *(u32x2 *)(p.out + ((long)n * p.M + m) * ppi + px) = v;
+                                }
                             }
-                            acc[mi][ni][j] = 0.f;
-                        }
                     }
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                            for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.f;
+                } else {
+                    // register j of lane l: channel 8*(j/4) + 4*(l/32) + j%4, pixel l%32 of the block
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const int m = m0 + mi * 32 + 8 * (j / 4) + 4 * half + (j % 4);
+                            const float bias = (p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
+#pragma unroll
+                            for (int ni = 0; ni < NI; ++ni) {
+                                const int n = n_base + pg[ni];
+                                if (m < p.M && pi[ni] >= 0 && n < p.N) {
+                                    const int h = pi[ni] * p.os + p.a0, w = pj[ni] * p.os + p.b0;
+                                    p.out[(((long)n * p.M + m) * p.Hout + h) * p.Wout + w] = f32_to_bf16(acc[mi][ni][j] + bias);
+                                }
+                                acc[mi][ni][j] = 0.f;
+                            }
+                        }
+                }
             }
         }
         if (++kb == p.nkb) {
@@ -314,9 +354,9 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     }
 }
 
-template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p, hipStream_t st)
+template <int NI, int WM, int WN, bool TR> hipError_t launch_gather_tr(const GatherParams &p, hipStream_t st)
 {
-    auto kern = conv_gather_kernel<NI, WM, WN>;
+    auto kern = conv_gather_kernel<NI, WM, WN, TR>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -327,6 +367,14 @@ template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p
     dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM);
     hipLaunchKernelGGL(kern, grid, dim3(512), (size_t)2 * p.patch_px * KCS * 2, st, p);
     return hipGetLastError();
+}
+
+template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p, hipStream_t st)
+{
+    // runs of 4 pixels are contiguous and 8-byte aligned: the class grid is the whole output
+    // plane and a plane is a multiple of 4 pixels
+    const bool packed = p.os == 1 && p.Hc == p.Hout && p.Wc == p.Wout && (p.Hc * p.Wc) % 4 == 0;
+    return packed ? launch_gather_tr<NI, WM, WN, true>(p, st) : launch_gather_tr<NI, WM, WN, false>(p, st);
 }
 
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
