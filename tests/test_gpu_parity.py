@@ -75,6 +75,20 @@ SMALL = [
     ("tiny 1px", 1, 1, 1, 1, 1, 1, 1, 1, 0, 2),
     ("k larger than map", 2, 3, 3, 3, 3, 3, 3, 1, 1, 4),
     ("wide channels", 2, 70, 33, 6, 6, 3, 3, 1, 1, 2),
+    # several images per pixel tile with a ragged last group; channels not a multiple of 32
+    ("4x4 maps batch 5", 5, 48, 40, 4, 4, 3, 3, 1, 1, 2),
+    ("8x8 maps batch 9", 9, 64, 64, 8, 8, 3, 3, 1, 1, 2),
+    ("7x7 maps batch 6", 6, 32, 96, 7, 7, 3, 3, 1, 1, 2),
+    # row lengths of 1, 2, 4 and 7 eight-pixel segments (compile-time row walks) and one that is none of them
+    ("row 14", 3, 32, 32, 14, 14, 3, 3, 1, 1, 2),
+    ("row 28", 2, 32, 64, 28, 28, 3, 3, 1, 1, 2),
+    ("row 56", 1, 16, 32, 56, 56, 3, 3, 1, 1, 4),
+    ("row 40", 1, 16, 16, 40, 40, 3, 3, 1, 1, 2),
+    # pixel split over the waves with an uneven number of row pairs; edge tiles in both channel dims
+    ("12x12 c72 k40", 3, 72, 40, 12, 12, 3, 3, 1, 1, 2),
+    ("s2 parity classes", 3, 32, 48, 16, 16, 3, 3, 2, 1, 2),
+    ("1x1 wide", 2, 128, 64, 14, 14, 1, 1, 1, 0, 2),
+    ("1x1 s2 wide", 2, 96, 160, 14, 14, 1, 1, 2, 0, 4),
 ]
 
 
