@@ -70,7 +70,8 @@ typedef enum cac_op {
     CAC_OP_BWD_WEIGHT_COMPRESSED = 1,
     CAC_OP_BWD_DATA = 2,
     CAC_OP_COMPRESS = 3,
-    CAC_OP_BWD_BIAS = 4
+    CAC_OP_BWD_BIAS = 4,
+    CAC_OP_GRAD_COSINE = 5
 } cac_op;
 
 /* One convolution layer with a compressed saved input.  Plain data, filled by
@@ -144,6 +145,15 @@ int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX,
 /* Bias gradient (bias-gradient formula in the same figure): db[o] = sum_{n,p,q} dY.
  * db [C_out] float is overwritten. */
 int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream);
+
+/* Layer sensitivity metric (the equation of the section "Layer sensitivity"): cosine
+ * similarity cos(a, b) = a.b / (|a| |b|) of two weight gradients of this layer, e.g. the one
+ * computed from the compressed activation against the exact one (pooling factor 1).
+ * dW_a, dW_b: [C_out][C_in][R][S] float, read only.  out: 4 floats on the device, written:
+ * {cos, a.b, |a|^2, |b|^2}; cos is 0 when either norm is 0.  Sums are taken in double
+ * precision in a fixed order.  ws: cac_workspace_size(d, CAC_OP_GRAD_COSINE) bytes. */
+int cac_grad_cosine(const cac_desc *d, const void *dW_a, const void *dW_b, void *out,
+                    void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

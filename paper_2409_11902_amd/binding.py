@@ -21,11 +21,11 @@ ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_ALIGNMENT, ERR_LA
 F32, BF16 = 0, 1
 NCHW, NHWC = 0, 1
 EDGE_CEIL_VALID, EDGE_FLOOR_DROP = 0, 1
-OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS = range(5)
+OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS, OP_GRAD_COSINE = range(6)
 
 EXPORTS = (
     "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size", "cac_describe_plan",
-    "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias",
+    "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias", "cac_grad_cosine",
 )
 
 
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.conv_bwd_weight_compressed.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_data.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_bias.argtypes = [dp, vp, vp, vp]
+        L.cac_grad_cosine.argtypes = [dp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         for n in EXPORTS[2:]:
             getattr(L, n).restype = ctypes.c_int
         _lib = L
@@ -166,6 +167,11 @@ def conv_bwd_data(d, W, dY, dX, ws=None, stream=None):
 
 def conv_bwd_bias(d, dY, db, stream=None):
     _check(lib().conv_bwd_bias(ctypes.byref(d), _ptr(dY), _ptr(db), _stream(stream)))
+
+
+def cac_grad_cosine(d, dW_a, dW_b, out, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().cac_grad_cosine(ctypes.byref(d), _ptr(dW_a), _ptr(dW_b), _ptr(out), wp, wb, _stream(stream)))
 
 
 # ---- host <-> device marshalling (type conversion only, no arithmetic)

@@ -96,6 +96,7 @@ static size_t workspace_bytes(const Geom &g, int dtype, int op)
     // channels-last copy of the input and the repacked filter
     if (op == CAC_OP_FWD_AND_COMPRESS) return conv_mfma_workspace(g, dtype, false);
     if (op == CAC_OP_BWD_DATA) return conv_mfma_workspace(g, dtype, true);
+    if (op == CAC_OP_GRAD_COSINE) return cosine_workspace((long)g.K * g.C * g.R * g.S);
     return 0;
 }
 
@@ -156,7 +157,7 @@ int cac_workspace_size(const cac_desc *d, int op, size_t *bytes)
     Geom g;
     int rc = make_geom(d, &g, true);
     if (rc) return rc;
-    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_BIAS) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_GRAD_COSINE) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     if (!bytes) return fail(CAC_ERR_INVALID_ARG, "bytes is NULL");
     *bytes = workspace_bytes(g, d->dtype, op);
     return CAC_OK;
@@ -168,7 +169,7 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
     int rc = make_geom(d, &g, true);
     if (rc) return rc;
     if (!buf || buf_len == 0) return fail(CAC_ERR_INVALID_ARG, "buf is NULL or empty");
-    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_BIAS) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_GRAD_COSINE) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     DwMfmaPlan plan;
     if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && dw_mfma_plan(g, d->dtype, &plan)) {
         const DwMfmaParams &p = plan.p;
@@ -246,6 +247,19 @@ int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream)
     if (rc) return rc;
     if ((rc = check_ptr(dY, "dY")) || (rc = check_ptr(db, "db"))) return rc;
     return launched(launch_db(g, d->dtype, dY, (float *)db, (hipStream_t)stream), "bias gradient");
+}
+
+int cac_grad_cosine(const cac_desc *d, const void *dW_a, const void *dW_b, void *out, void *ws, size_t ws_bytes,
+                    void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(dW_a, "dW_a")) || (rc = check_ptr(dW_b, "dW_b")) || (rc = check_ptr(out, "out"))) return rc;
+    if ((rc = check_ws(g, d->dtype, CAC_OP_GRAD_COSINE, ws, ws_bytes, nullptr))) return rc;
+    return launched(launch_cosine((const float *)dW_a, (const float *)dW_b, (long)g.K * g.C * g.R * g.S, (float *)out, ws,
+                                  (hipStream_t)stream),
+                    "gradient cosine");
 }
 
 } // extern "C"

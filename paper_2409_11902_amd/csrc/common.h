@@ -51,5 +51,7 @@ hipError_t launch_fwd_generic(const Geom &g, int dtype, const void *X, const voi
 hipError_t launch_dx_generic(const Geom &g, int dtype, const void *W, const void *dY, void *dX, hipStream_t st);
 hipError_t launch_dw_generic(const Geom &g, int dtype, const void *Z, const void *dY, float *dW, hipStream_t st);
 hipError_t launch_db(const Geom &g, int dtype, const void *dY, float *db, hipStream_t st);
+size_t cosine_workspace(long n);
+hipError_t launch_cosine(const float *a, const float *b, long n, float *out, void *ws, hipStream_t st);
 
 } // namespace cac

@@ -130,6 +130,12 @@ def test_null_and_misaligned_pointers_fail_before_any_launch():
     assert L.conv_bwd_data(p, None, a, a, None, 0, None) == B.ERR_INVALID_ARG
     assert L.conv_bwd_bias(p, a, None, None) == B.ERR_INVALID_ARG
     assert b"NULL" in L.cac_last_error()
+    need = B.cac_workspace_size(d, B.OP_GRAD_COSINE)
+    assert need > 0
+    assert L.cac_grad_cosine(p, a, None, a, a, need, None) == B.ERR_INVALID_ARG
+    assert L.cac_grad_cosine(p, a, a, m, a, need, None) == B.ERR_ALIGNMENT
+    assert L.cac_grad_cosine(p, a, a, a, a, need - 1, None) == B.ERR_WORKSPACE_TOO_SMALL
+    assert L.cac_grad_cosine(p, a, a, a, None, 0, None) == B.ERR_WORKSPACE_TOO_SMALL
 
 
 def test_workspace_too_small_is_reported():

@@ -175,6 +175,41 @@ def test_invariants_on_device(dtype):
                                rtol=1e-5 if dtype == synth.F32 else 4e-3)
 
 
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_gradient_cosine(dtype):
+    """Layer sensitivity metric: cosine of the weight gradient from the compressed activation
+    against the exact one, computed on the device, against the oracle's."""
+    import torch
+    from gpu_util import run_step, upload, workspace, Guarded
+    from paper_2409_11902_amd import binding as B
+    spec = synth.LayerSpec("cos", 3, 24, 40, 14, 14, 3, 3, 1, 1, 2, dtype)
+    t = synth.make_inputs(spec, "cos")
+    lossy, exact = run_step(spec, t), run_step(spec.with_k(1), t)
+    d = lossy["desc"]
+    a, b = upload(lossy["dW"].astype(np.float32), synth.F32), upload(exact["dW"].astype(np.float32), synth.F32)
+    out = Guarded((4,), torch.float32)
+    for _ in range(2):  # twice: the workspace is reused, the result must not change
+        B.cac_grad_cosine(d, a, b, out.t, workspace(d, B.OP_GRAD_COSINE))
+    torch.cuda.synchronize()
+    out.check("cosine")
+    got = out.t.cpu().numpy().astype(np.float64)
+    # (a) the reduction itself: against fp64 sums of the very same device gradients
+    av, bv = lossy["dW"].ravel(), exact["dW"].ravel()
+    np.testing.assert_allclose(got[1:], [av @ bv, av @ av, bv @ bv], rtol=2e-6)
+    assert abs(got[0] - oracle.cosine(lossy["dW"], exact["dW"])) <= 2e-6
+    # (b) the metric end to end: against the oracle's gradients from the oracle's pooled map
+    g = geom(spec)
+    X, dY = t["X"].astype(np.float64), t["dY"].astype(np.float64)
+    xh = oracle.inflate(oracle.avgpool(X, 2, 2), spec.H, spec.W, 2, 2)
+    want = oracle.cosine(oracle.conv_dw(g, xh, dY), oracle.conv_dw(g, X, dY))
+    assert 0.3 < want < 0.999   # compression changes the direction, but not arbitrarily
+    assert abs(got[0] - want) <= (1e-5 if dtype == synth.F32 else 2e-3)
+    # degenerate input: a zero gradient has no direction
+    B.cac_grad_cosine(d, a, torch.zeros_like(b), out.t, workspace(d, B.OP_GRAD_COSINE))
+    torch.cuda.synchronize()
+    assert out.t[0].item() == 0.0
+
+
 def test_no_bias_and_empty_free_paths():
     from gpu_util import run_step
     spec = synth.LayerSpec("nobias", 2, 4, 6, 8, 8, 3, 3, 1, 1, 2, synth.F32)
