@@ -239,6 +239,9 @@ def main():
         del xs
         comp.append((warm_ms, cold_ms))
 
+    # ---- gradient quality (untimed): cosine of dW from the pooled map against the exact dW
+    cosines = [grad_cosine(L, B, synth, torch, stream) for L in layers]
+
     # ---- report
     tot_flops = sum(sum(L.flops.values()) for L in layers)
     dw_flops = sum(L.flops["dw"] for L in layers)
@@ -256,7 +259,7 @@ def main():
                           "dw_in_step_us": round(acc["dw_in_step"][i] * 1e3, 2),
                           "fwd_compress_us": round(acc["fwd+compress"][i] * 1e3, 2), "dx_us": round(acc["dx"][i] * 1e3, 2),
                           "compress_cold_gbps": round(cg, 1), "compress_warm_gbps": round(wg, 1),
-                          "x_bytes": L.x_bytes, "z_bytes": L.z_bytes})
+                          "x_bytes": L.x_bytes, "z_bytes": L.z_bytes, "dw_cosine_vs_exact": round(cosines[i], 5)})
     dw_tflops = dw_flops / (sum(dw_ms) * 1e-3) / 1e12
     comp_bytes = sum(L.bytes["compress"] for L in layers)
     comp_cold_gbps = comp_bytes / (sum(c for _, c in comp) * 1e-3) / 1e9
@@ -309,6 +312,24 @@ def main():
 
 
 DW_LAUNCHES = 200
+
+
+def grad_cosine(L, B, synth, torch, stream):
+    """Cosine similarity (the paper's layer-sensitivity metric) between the weight gradient
+    computed from the pooled map and the exact one (the same call with pooling factor 1, whose
+    saved activation is X itself), all on the device."""
+    spec1 = L.spec.with_k(1)
+    d1 = B.desc_from_spec(spec1)
+    n = B.cac_workspace_size(d1, B.OP_BWD_WEIGHT_COMPRESSED)
+    ws1 = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda:0")
+    dW1 = torch.empty_like(L.dW)
+    B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], stream)
+    B.conv_bwd_weight_compressed(d1, L.X, L.dY, dW1, ws1, stream)
+    out = torch.empty(4, dtype=torch.float32, device="cuda:0")
+    wsc = torch.empty(B.cac_workspace_size(L.d, B.OP_GRAD_COSINE), dtype=torch.uint8, device="cuda:0")
+    B.cac_grad_cosine(L.d, L.dW, dW1, out, wsc, stream)
+    torch.cuda.synchronize()
+    return float(out[0].item())
 
 
 def time_dw(layers, B, torch, stream):
