@@ -39,42 +39,111 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 
 // ---- repacks ---------------------------------------------------------------------
 
-// in [N][C][HW] -> out [N][HW][Cp], zeros for c >= C.  One block: 64 pixels x 64 channels.
-__global__ void __launch_bounds__(256) nchw_to_nhwc_kernel(const bf16_t *__restrict__ in, bf16_t *__restrict__ out, int C,
-                                                           int HW, int Cp)
+// Both repacks of a call in one launch.
+//
+// Input: in [N][C][HW] -> out [N][HW][Cp], zeros for c >= C.
+//   HW a multiple of 8: a thread moves an 8 channel x 8 pixel block: eight 16-byte loads along
+//   the pixels (consecutive lanes = consecutive pixel groups of a channel row), an 8 x 8
+//   transpose in registers (v_perm), eight 16-byte stores of 8 channels each.
+//   Otherwise: 64 x 64 tiles through LDS, element by element.
+// Filter: W [O][C][R][S] -> Wt in MFMA fragment order [R*S][KCp/16][Mp/32][lane 64][8]: lane l of
+//   a wave holds row m = 32*mblk + l%32 and the 8 channels kc = 16*kblk + 8*(l/32) ..., so a wave
+//   reads the A fragment of a (tap, 16-channel block, 32-row block) as one contiguous KiB.
+//   Forward: m = o, kc = c; data gradient: m = c, kc = o.
+// Blocks [0, in_blocks) do the input, the rest the filter.
+struct RepackParams {
+    const bf16_t *in;
+    bf16_t *out;
+    int N, C, HW, Cp, in_blocks, fast;
+    const bf16_t *W;
+    bf16_t *Wt;
+    int O, Cw, RS, Mp, KCp, transpose;
+};
+
+__global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
 {
     __shared__ bf16_t tile[64][66];
-    const int n = blockIdx.z, c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
+    if ((int)blockIdx.x >= p.in_blocks) {
+        const long total = (long)p.RS * p.Mp * p.KCp;
+        const long idx = (long)(blockIdx.x - p.in_blocks) * 256 + threadIdx.x;
+        if (idx >= total) return;
+        const int e = idx & 7, lane = (idx >> 3) & 63;
+        long rest = idx >> 9;
+        const int mblk = rest % (p.Mp / 32);
+        rest /= p.Mp / 32;
+        const int kblk = rest % (p.KCp / 16), tap = rest / (p.KCp / 16);
+        const int m = mblk * 32 + (lane & 31), kc = kblk * 16 + 8 * (lane >> 5) + e;
+        const int o = p.transpose ? kc : m, c = p.transpose ? m : kc;
+        p.Wt[idx] = (o < p.O && c < p.Cw) ? p.W[((long)o * p.Cw + c) * p.RS + tap] : (bf16_t)0;
+        return;
+    }
+    if (p.fast) {
+        // item -> (image n, block of up to 8 channel groups, pixel group pg of 8, channel group
+        // within the block), the last fastest: 8 neighbouring lanes read 8 channel rows and
+        // write the 128 contiguous bytes of 64 channels of one pixel; the next lanes move along
+        // the pixels, so every row is read in 128-byte runs too
+        const int pgs = p.HW / 8, cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
+        const long item = (long)blockIdx.x * 256 + threadIdx.x;
+        if (item >= (long)p.N * cgb * pgs * cgw) return;
+        const int cl = item % cgw;
+        long t1 = item / cgw;
+        const int pg = t1 % pgs;
+        t1 /= pgs;
+        const int cg = (int)(t1 % cgb) * cgw + cl, n = t1 / cgb;
+        if (cg >= cgs) return;
+        const rsrc_t rs = make_rsrc(p.in, (uint32_t)p.N * p.C * p.HW * 2u);
+        u32x4 r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = cg * 8 + i;
+            const uint32_t e = ((uint32_t)(n * p.C + c) * p.HW + pg * 8) * 2u;
+            r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, c < p.C ? e : kNoLoad, 0, 0);
+        }
+        bf16_t *dst = p.out + ((long)n * p.HW + pg * 8) * p.Cp + cg * 8;
+#pragma unroll
+        for (int px = 0; px < 8; ++px) {
+            // pixel px of the 8 channels: half px%2 of dword px/2 of every row
+            u32x4 v;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t lo = r[2 * k][px / 2], hi = r[2 * k + 1][px / 2];
+                v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            }
+            *(u32x4 *)(dst + (long)px * p.Cp) = v;
+        }
+        return;
+    }
+    // block -> (image, 64-channel block, 64-pixel block)
+    const int pbs = (p.HW + 63) / 64, cbs = (p.Cp + 63) / 64;
+    const int pb = blockIdx.x % pbs, t1 = blockIdx.x / pbs;
+    const int cb = t1 % cbs, n = t1 / cbs;
+    const int c0 = cb * 64, p0 = pb * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int k = ty; k < 64; k += 4) {
         const int c = c0 + k, px = p0 + tx;
-        tile[k][tx] = (c < C && px < HW) ? in[((long)n * C + c) * HW + px] : (bf16_t)0;
+        tile[k][tx] = (c < p.C && px < p.HW) ? p.in[((long)n * p.C + c) * p.HW + px] : (bf16_t)0;
     }
     __syncthreads();
     for (int k = ty; k < 64; k += 4) {
         const int px = p0 + k, c = c0 + tx;
-        if (px < HW && c < Cp) out[((long)n * HW + px) * Cp + c] = tile[tx][k];
+        if (px < p.HW && c < p.Cp) p.out[((long)n * p.HW + px) * p.Cp + c] = tile[tx][k];
     }
 }
 
-// W [O][C][R][S] -> Wt in MFMA fragment order [R*S][KCp/16][Mp/32][lane 64][8]: lane l of a wave
-// holds row m = 32*mblk + l%32 and the 8 channels kc = 16*kblk + 8*(l/32) ..., so a wave reads the
-// A fragment of a (tap, 16-channel block, 32-row block) as one contiguous KiB.
-// Forward: m = o, kc = c; data gradient: m = c, kc = o.
-__global__ void __launch_bounds__(256) filter_repack_kernel(const bf16_t *__restrict__ W, bf16_t *__restrict__ Wt, int O, int C,
-                                                            int RS, int Mp, int KCp, int transpose)
+// Launches the input and filter repacks of one call.
+hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, int Cp, const bf16_t *W, bf16_t *Wt, int O,
+                         int Cw, int RS, int Mp, int KCp, int transpose, hipStream_t st)
 {
-    const long total = (long)RS * Mp * KCp;
-    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int e = idx & 7, lane = (idx >> 3) & 63;
-    long rest = idx >> 9;
-    const int mblk = rest % (Mp / 32);
-    rest /= Mp / 32;
-    const int kblk = rest % (KCp / 16), tap = rest / (KCp / 16);
-    const int m = mblk * 32 + (lane & 31), kc = kblk * 16 + 8 * (lane >> 5) + e;
-    const int o = transpose ? kc : m, c = transpose ? m : kc;
-    Wt[idx] = (o < O && c < C) ? W[((long)o * C + c) * RS + tap] : (bf16_t)0;
+    RepackParams p{};
+    p.in = in; p.out = out; p.N = N; p.C = C; p.HW = HW; p.Cp = Cp;
+    p.fast = HW % 8 == 0;
+    const int cgs = Cp / 8, cgw = cgs < 8 ? cgs : 8;
+    const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (HW / 8) : 0;
+    p.in_blocks = p.fast ? (int)((items + 255) / 256) : N * ((Cp + 63) / 64) * ((HW + 63) / 64);
+    p.W = W; p.Wt = Wt; p.O = O; p.Cw = Cw; p.RS = RS; p.Mp = Mp; p.KCp = KCp; p.transpose = transpose;
+    const long wtotal = (long)RS * Mp * KCp;
+    hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(p.in_blocks + (wtotal + 255) / 256)), dim3(256), 0, st, p);
+    return hipGetLastError();
 }
 
 __global__ void __launch_bounds__(256) zero_fill_kernel(u32x4 *dst, long n16)
@@ -495,12 +564,9 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     if (!shape_gather(p, &variant)) return false;
     const size_t in_bytes = ((size_t)g.N * g.H * g.W * p.KCp * 2 + 255) / 256 * 256;
     bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + in_bytes);
-    const int HW = g.H * g.W;
-    hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3((HW + 63) / 64, (p.KCp + 63) / 64, g.N), dim3(256), 0, st,
-                       (const bf16_t *)X, in, g.C, HW, p.KCp);
-    const long wtotal = (long)p.ntaps_total * p.Mp * p.KCp;
-    hipLaunchKernelGGL(filter_repack_kernel, dim3((unsigned)((wtotal + 255) / 256)), dim3(256), 0, st, (const bf16_t *)W, wt,
-                       g.K, g.C, p.ntaps_total, p.Mp, p.KCp, 0);
+    *err = launch_repack((const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total,
+                         p.Mp, p.KCp, 0, st);
+    if (*err != hipSuccess) return true;
     p.in = in; p.wt = wt; p.bias = (const bf16_t *)b; p.out = (bf16_t *)Y;
     *err = run_gather(p, variant, st);
     return true;
@@ -546,13 +612,8 @@ bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, voi
         const long n16 = ((long)g.N * g.C * g.H * g.W * 2 + 15) / 16; // tensor allocations are 16-byte granular
         hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (u32x4 *)dX, n16);
     }
-    const int PQ = g.P * g.Q;
-    hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3((PQ + 63) / 64, (base.KCp + 63) / 64, g.N), dim3(256), 0, st,
-                       (const bf16_t *)dY, in, g.K, PQ, base.KCp);
-    const long wtotal = (long)base.ntaps_total * base.Mp * base.KCp;
-    hipLaunchKernelGGL(filter_repack_kernel, dim3((unsigned)((wtotal + 255) / 256)), dim3(256), 0, st, (const bf16_t *)W, wt,
-                       g.K, g.C, base.ntaps_total, base.Mp, base.KCp, 1);
-    *err = hipGetLastError();
+    *err = launch_repack((const bf16_t *)dY, in, g.N, g.K, g.P * g.Q, base.KCp, (const bf16_t *)W, wt, g.K, g.C,
+                         base.ntaps_total, base.Mp, base.KCp, 1, st);
     for (int k = 0; k < ncls && *err == hipSuccess; ++k) {
         cls[k].in = in; cls[k].wt = wt; cls[k].bias = nullptr; cls[k].out = (bf16_t *)dX;
         *err = run_gather(cls[k], variant[k], st);
