@@ -15,14 +15,13 @@ struct DwMfmaParams {
     int LR, LRpad;       // rows per chunk, rounded up to even
     int SEGS, Qpad;      // 8-pixel segments per output row
     int NZ;              // Z-row slots per image and chunk
-    int XB, XW, PW;      // xhat blocks with data per row; LDS width of a row (all phases) and of one phase
+    int XW, PW;          // LDS width of an xhat row (all phases) and of one phase
     int ZV;              // 4-element vectors per Z row
     int rowitems, citems;         // 16-byte dY items per output channel; 8-byte Z items per input channel
     int LDY, ldy_log2, dy_passes; // lanes sharing an output channel in the dY copy; passes per chunk
     int LPC, lpc_log2, z_passes;  // same for the Z copy
     int dy_ostride, x_cstride;    // LDS elements per output channel / per input channel
     int lds_bytes;
-    int dy_vec, z_vec;   // widest aligned global vector (elements)
     uint32_t m_segs, m_pr, m_zv, m_nz, m_rb;
     int nchunks, chunks_per_slice, nslices;
     int tile_o, tile_c;  // workgroup tile

@@ -59,7 +59,7 @@ template <int ha, int hb> __device__ __forceinline__ uint32_t halves(uint32_t a,
 // 16 bytes of LDS at an absolute LDS byte address (saves the compiler adding the
 // base of the dynamic LDS block, unknown until link time, to every access).
 typedef __attribute__((address_space(3))) const u32x4 *lds_u32x4_ptr;
-__device__ __forceinline__ u32x4 lds16(uint32_t addr) { return *(lds_u32x4_ptr)addr; }
+__device__ __forceinline__ u32x4 lds16(uint32_t addr) { return *(lds_u32x4_ptr)(uintptr_t)addr; }
 
 constexpr int kMaxDy = 8; // 16-byte dY items a thread moves per chunk
 constexpr int kMaxZ = 4;  // 16-byte Z items a thread moves per chunk
@@ -100,23 +100,18 @@ template <int NB, int SG, int PAD, int s> __device__ __forceinline__ bf16x8 make
     return f.v;
 }
 
-// Global reads go through buffer loads: a lane whose byte offset is kNoLoad (or
-// anything at or beyond the tensor's size) gets zeros back without touching
-// memory and without a branch, so every load of a chunk can be in flight at once.
-constexpr uint32_t kNoLoad = 0x80000000u; // tensors on this path are smaller than 2 GiB
+// Global reads go through buffer loads: a lane whose byte offset lies at or beyond
+// the tensor's size gets zeros back without touching memory and without a branch,
+// so every load of a chunk can be in flight at once (tensors on this path are
+// smaller than 2 GiB; offsets from 2^31 on mean "no load").
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
 }
 
-// 8 consecutive bf16 starting at ELEMENT offset e of a tensor, as they arrive:
-// the 4 dwords from the dword-aligned address down from it (rows of odd length
-// start on odd elements).  Always one 16-byte load.
-__device__ __forceinline__ u32x4 load_raw8(rsrc_t rs, uint32_t e, bool live)
-{
-    return __builtin_amdgcn_raw_buffer_load_b128(rs, live ? (e & ~1u) * 2u : kNoLoad, 0, 0);
-}
+// Items are read with one 16-byte load each from the dword-aligned address at or below
+// their first element (rows of odd length start on odd elements).
 // The 8 elements themselves.  After an odd start everything moves down by one
 // element and the last one comes from the first dword of the next item of the
 // same row, which the next lane holds (the copy maps consecutive items of a row
@@ -810,13 +805,6 @@ __global__ void __launch_bounds__(256) dw_reduce_tile_kernel(const float *__rest
 
 uint32_t magic_of(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
 
-int largest_vec(int extent, int cap)
-{
-    int v = 1;
-    while (v < cap && extent % (2 * v) == 0) v *= 2;
-    return v;
-}
-
 // Kernel table: filter/stride family x workgroup shape.
 struct Variant {
     int R, SG, MI, NI, WM, WN, KS;
@@ -890,7 +878,6 @@ bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
     base.kh_log2 = khl; base.kw_log2 = kwl;
     base.SEGS = (g.Q + 7) / 8;
     base.Qpad = base.SEGS * 8;
-    base.XB = (g.W + 7) / 8;
     base.ZV = (g.Wp + 7) / 8;
     const int NPH = g.S == 1 ? 1 : g.sh;  // xhat column phases kept per row
     // width of one phase of an xhat row in LDS: the padded output row, or what the
@@ -960,9 +947,6 @@ bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
     p.m_zv = magic_of(p.ZV);
     p.m_nz = magic_of(p.NZ);
     p.m_rb = magic_of(p.RB);
-    // widest aligned vector for the global reads (tensor bases are 16-byte aligned)
-    p.dy_vec = largest_vec(g.Q, 8);   // (informational: every read is a 16-byte load)
-    p.z_vec = largest_vec(g.Wp, 8);
 
     p.tiles_o = (g.K + tile_o - 1) / tile_o;
     p.tiles_c = (g.C + tile_c - 1) / tile_c;
