@@ -233,12 +233,14 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         put(0, ra);
         __syncthreads();
         for (int s = 0; s < nstages; s += 2) {
+            // (a stage past the end is written all the same -- zeros into a buffer nobody reads
+            // any more -- so that every path consumes every load)
             fetch(s + 2, ra);
-            if (s + 1 < nstages) put(buf_bytes, rb);
+            put(buf_bytes, rb);
             __syncthreads();
             if (s + 1 >= nstages) break;
             fetch(s + 3, rb);
-            if (s + 2 < nstages) put(0, ra);
+            put(0, ra);
             __syncthreads();
         }
         return;

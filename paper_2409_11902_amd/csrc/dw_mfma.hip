@@ -285,6 +285,13 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         const int cw = __builtin_amdgcn_readfirstlane(tid >> 6); // index among the copy waves
         // ---- registers -> LDS buffer at element offset `base` (with the horizontal inflation)
         auto stage = [&](int ci, uint32_t base, const u32x4 (&rdy)[kMaxDy], const u32x4 (&rz)[kMaxZ]) {
+            // Everything but the kMaxDy + kMaxZ loads of the younger chunk has arrived.  Said
+            // explicitly: items past the last pass are loaded but never looked at, and the
+            // compiler, seeing loads nobody waited for, would otherwise drain the whole queue
+            // before reusing their registers.  (s_waitcnt operand: vmcnt in bits 3:0 and 15:14,
+            // the other counters left at their maximum.)
+            constexpr int kYounger = kMaxDy + kMaxZ;
+            __builtin_amdgcn_s_waitcnt((kYounger & 0xF) | ((kYounger >> 4) << 14) | 0x0F70);
             const Src s = src_of(ci);
             // row table: entry rho = {dY row offset, xhat row offset per filter row (the zero
             // slot for rows outside the image)}, in elements from the lane's channel base
@@ -391,21 +398,27 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         };
 
         u32x4 dyA[kMaxDy], zA[kMaxZ], dyB[kMaxDy], zB[kMaxZ];
+        // Two chunks of loads are in flight.  A register set is refilled right after it has been
+        // staged, in the same straight-line code, so that the compiler sees every load consumed
+        // before its register is reused and never has to drain the other set's loads.
         fetch(ci_begin, true, dyA, zA); // (every workgroup has at least one chunk)
         fetch(ci_begin + 1, ci_begin + 1 < ci_end, dyB, zB);
         zero_fill(); // in the shadow of the first loads
         __syncthreads();
         stage(ci_begin, base0, dyA, zA);
+        fetch(ci_begin + 2, ci_begin + 2 < ci_end, dyA, zA);
         __syncthreads(); // buffer 0 holds the first chunk
         for (int ci = ci_begin; ci < ci_end; ci += 2) {
-            // MFMA waves are on buffer 0 (chunk ci); set B holds chunk ci+1
-            fetch(ci + 2, ci + 2 < ci_end, dyA, zA);
-            if (ci + 1 < ci_end) stage(ci + 1, base1, dyB, zB);
+            // MFMA waves are on buffer 0 (chunk ci); set B holds chunk ci+1, set A chunk ci+2.
+            // (A chunk past the end is staged all the same -- zeros into a buffer nobody reads
+            // any more -- so that every path consumes every load.)
+            stage(ci + 1, base1, dyB, zB);
+            fetch(ci + 3, ci + 3 < ci_end, dyB, zB);
             __syncthreads();
             if (ci + 1 >= ci_end) break;
-            // MFMA waves are on buffer 1 (chunk ci+1); set A holds chunk ci+2
-            fetch(ci + 3, ci + 3 < ci_end, dyB, zB);
-            if (ci + 2 < ci_end) stage(ci + 2, base0, dyA, zA);
+            // MFMA waves are on buffer 1 (chunk ci+1); set A holds chunk ci+2, set B chunk ci+3
+            stage(ci + 2, base0, dyA, zA);
+            fetch(ci + 4, ci + 4 < ci_end, dyA, zA);
             __syncthreads();
         }
         if constexpr (KS > 1) __syncthreads(); // the barrier inside the MFMA waves' cross-wave sum

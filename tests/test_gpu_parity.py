@@ -224,6 +224,58 @@ def test_weight_gradient_is_reproducible_bit_for_bit():
         assert np.array_equal(first, run_step(spec, t)["dW"])
 
 
+def test_graph_capture_and_side_stream():
+    """The three calls enqueue on the caller's stream only and record no memset nodes: captured
+    in a HIP graph on a side stream and replayed several times, with eager work and
+    synchronisations in between, every replay reproduces the eager result."""
+    import torch
+    from gpu_util import upload, workspace
+    from paper_2409_11902_amd import binding as B
+    spec = synth.LayerSpec("graph", 6, 40, 72, 14, 14, 3, 3, 2, 1, 2, synth.BF16)   # stride 2: dX clears + 4 classes
+    t = synth.make_inputs(spec, "graph")
+    d = B.desc_from_spec(spec)
+    hp, wp, _, _ = B.cac_pooled_shape(d)
+    X, Wt, b, dY = (upload(t[k], spec.dtype) for k in ("X", "W", "b", "dY"))
+    bf = torch.bfloat16
+    Y = torch.empty((spec.N, spec.K, spec.P, spec.Q), dtype=bf, device="cuda:0")
+    Z = torch.empty((spec.N, spec.C, hp, wp), dtype=bf, device="cuda:0")
+    dW = torch.empty((spec.K, spec.C, 3, 3), dtype=torch.float32, device="cuda:0")
+    dX = torch.empty((spec.N, spec.C, spec.H, spec.W), dtype=bf, device="cuda:0")
+    ws = [workspace(d, op) for op in (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA)]
+
+    def step(stream):
+        B.conv_fwd_and_compress(d, X, Wt, b, Y, Z, ws[0], stream)
+        B.conv_bwd_weight_compressed(d, Z, dY, dW, ws[1], stream)
+        B.conv_bwd_data(d, Wt, dY, dX, ws[2], stream)
+
+    outs = (Y, Z, dW, dX)
+    step(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(side)                                  # eager on the side stream
+        side.synchronize()
+        for o, w in zip(outs, want):
+            assert torch.equal(o, w)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step(side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float("nan"))                   # eager work between replays
+        for w in ws:
+            if w is not None:
+                w.random_(0, 255)                   # the workspace carries nothing between calls
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, w in zip(outs, want):
+            assert torch.equal(o, w), f"replay {rep}"
+
+
 def test_no_bias_and_empty_free_paths():
     from gpu_util import run_step
     spec = synth.LayerSpec("nobias", 2, 4, 6, 8, 8, 3, 3, 1, 1, 2, synth.F32)
