@@ -197,9 +197,11 @@ int conv_fwd_and_compress(const cac_desc *d, const void *X, const void *W, const
     if ((rc = check_ws(g, d->dtype, CAC_OP_FWD_AND_COMPRESS, ws, ws_bytes, nullptr))) return rc;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    if (!launch_fwd_mfma(g, d->dtype, X, W, d->has_bias ? b : nullptr, Y, ws, st, &e))
+    bool pooled = false;
+    if (!launch_fwd_mfma(g, d->dtype, X, W, d->has_bias ? b : nullptr, Y, Z, ws, st, &e, &pooled))
         e = launch_fwd_generic(g, d->dtype, X, W, d->has_bias ? b : nullptr, Y, st);
     if ((rc = launched(e, "forward convolution"))) return rc;
+    if (pooled) return CAC_OK;
     return launched(do_compress(g, d->dtype, X, Z, st), "compress");
 }
 

@@ -23,8 +23,8 @@ struct GatherParams {
 };
 
 size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad);
-bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *ws,
-                     hipStream_t st, hipError_t *err);
+bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *Z, void *ws,
+                     hipStream_t st, hipError_t *err, bool *pooled);
 bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,
                     hipError_t *err);
 

@@ -55,6 +55,8 @@ struct RepackParams {
     const bf16_t *in;
     bf16_t *out;
     int N, C, HW, Cp, in_blocks, fast;
+    bf16_t *Z;          // pooled copy of `in` written on the way (2 x 2 means), or null
+    int Wimg;           // image width (only with Z)
     const bf16_t *W;
     bf16_t *Wt;
     int O, Cw, RS, Mp, KCp, transpose;
@@ -81,35 +83,77 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
         // item -> (image n, block of up to 8 channel groups, pixel group pg of 8, channel group
         // within the block), the last fastest: 8 neighbouring lanes read 8 channel rows and
         // write the 128 contiguous bytes of 64 channels of one pixel; the next lanes move along
-        // the pixels, so every row is read in 128-byte runs too
-        const int pgs = p.HW / 8, cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
+        // the pixels, so every row is read in 128-byte runs too.  With Z, an item is the same 8
+        // pixels of TWO image rows (2h, 2h+1), from which it also forms the 2 x 2 means.
+        const bool pool = p.Z != nullptr;
+        const int wgs = pool ? p.Wimg / 8 : 1;                 // pixel groups per image row
+        const int pgs = pool ? p.HW / 16 : p.HW / 8;           // items along the pixels
+        const int cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
         const long item = (long)blockIdx.x * 256 + threadIdx.x;
         if (item >= (long)p.N * cgb * pgs * cgw) return;
         const int cl = item % cgw;
         long t1 = item / cgw;
-        const int pg = t1 % pgs;
+        const int pi = t1 % pgs;
         t1 /= pgs;
         const int cg = (int)(t1 % cgb) * cgw + cl, n = t1 / cgb;
         if (cg >= cgs) return;
+        // first pixel of the item's (first) row segment
+        const int hh = pool ? pi / wgs : 0, wg = pool ? pi - hh * wgs : 0;
+        const int px0 = pool ? (2 * hh * wgs + wg) * 8 : pi * 8;
         const rsrc_t rs = make_rsrc(p.in, (uint32_t)p.N * p.C * p.HW * 2u);
-        u32x4 r[8];
+        u32x4 r[2][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = cg * 8 + i;
-            const uint32_t e = ((uint32_t)(n * p.C + c) * p.HW + pg * 8) * 2u;
-            r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, c < p.C ? e : kNoLoad, 0, 0);
-        }
-        bf16_t *dst = p.out + ((long)n * p.HW + pg * 8) * p.Cp + cg * 8;
+        for (int a = 0; a < 2; ++a) {
+            if (a == 1 && !pool) break;
 #pragma unroll
-        for (int px = 0; px < 8; ++px) {
-            // pixel px of the 8 channels: half px%2 of dword px/2 of every row
-            u32x4 v;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint32_t lo = r[2 * k][px / 2], hi = r[2 * k + 1][px / 2];
-                v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            for (int i = 0; i < 8; ++i) {
+                const int c = cg * 8 + i;
+                const uint32_t e = ((uint32_t)(n * p.C + c) * p.HW + px0 + a * p.Wimg) * 2u;
+                r[a][i] = __builtin_amdgcn_raw_buffer_load_b128(rs, c < p.C ? e : kNoLoad, 0, 0);
             }
-            *(u32x4 *)(dst + (long)px * p.Cp) = v;
+        }
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            if (a == 1 && !pool) break;
+            bf16_t *dst = p.out + ((long)n * p.HW + px0 + a * p.Wimg) * p.Cp + cg * 8;
+#pragma unroll
+            for (int px = 0; px < 8; ++px) {
+                // pixel px of the 8 channels: half px%2 of dword px/2 of every row
+                u32x4 v;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t lo = r[a][2 * k][px / 2], hi = r[a][2 * k + 1][px / 2];
+                    v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                }
+                *(u32x4 *)(dst + (long)px * p.Cp) = v;
+            }
+        }
+        if (pool) {
+            // Z[n][c][hh][4*wg .. +3]: the same sum order and rounding as the stand-alone kernel
+            const int Hp = p.HW / p.Wimg / 2, Wp = p.Wimg / 2;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = cg * 8 + i;
+                if (c >= p.C) break;
+                uint32_t o[2];
+#pragma unroll
+                for (int j2 = 0; j2 < 2; ++j2) {
+                    uint32_t h2[2];
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        const uint32_t t0 = r[0][i][2 * j2 + jj], t1r = r[1][i][2 * j2 + jj];
+                        float sum = 0.f;
+                        sum += __uint_as_float(t0 << 16);
+                        sum += __uint_as_float(t0 & 0xffff0000u);
+                        sum += __uint_as_float(t1r << 16);
+                        sum += __uint_as_float(t1r & 0xffff0000u);
+                        h2[jj] = f32_to_bf16(sum * 0.25f);
+                    }
+                    o[j2] = h2[0] | (h2[1] << 16);
+                }
+                typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+                *(u32x2 *)(p.Z + (((long)n * p.C + c) * Hp + hh) * Wp + wg * 4) = u32x2{o[0], o[1]};
+            }
         }
         return;
     }
@@ -131,14 +175,16 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
 }
 
 // Launches the input and filter repacks of one call.
+// Z, Wimg: see RepackParams (Z null: no pooling; else HW must be a multiple of 2*Wimg and Wimg of 8).
 hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, int Cp, const bf16_t *W, bf16_t *Wt, int O,
-                         int Cw, int RS, int Mp, int KCp, int transpose, hipStream_t st)
+                         int Cw, int RS, int Mp, int KCp, int transpose, bf16_t *Z, int Wimg, hipStream_t st)
 {
     RepackParams p{};
     p.in = in; p.out = out; p.N = N; p.C = C; p.HW = HW; p.Cp = Cp;
+    p.Z = Z; p.Wimg = Wimg;
     p.fast = HW % 8 == 0;
     const int cgs = Cp / 8, cgw = cgs < 8 ? cgs : 8;
-    const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (HW / 8) : 0;
+    const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z ? HW / 16 : HW / 8) : 0;
     p.in_blocks = p.fast ? (int)((items + 255) / 256) : N * ((Cp + 63) / 64) * ((HW + 63) / 64);
     p.W = W; p.Wt = Wt; p.O = O; p.Cw = Cw; p.RS = RS; p.Mp = Mp; p.KCp = KCp; p.transpose = transpose;
     const long wtotal = (long)RS * Mp * KCp;
@@ -548,9 +594,12 @@ size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad)
 }
 
 // Forward: Y = X * W + b.  False when the geometry is not covered.
-bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *ws,
-                     hipStream_t st, hipError_t *err)
+// *pooled: Z has been written on the way (the channels-last repack reads X anyway); otherwise
+// the caller runs the compress kernel.
+bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *Z, void *ws,
+                     hipStream_t st, hipError_t *err, bool *pooled)
 {
+    *pooled = false;
     if (!supported(g, dtype)) return false;
     GatherParams p{};
     p.N = g.N; p.M = g.K; p.Mp = round_up(g.K, 64); p.KCp = round_up(g.C, 16);
@@ -566,8 +615,11 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     if (!shape_gather(p, &variant)) return false;
     const size_t in_bytes = ((size_t)g.N * g.H * g.W * p.KCp * 2 + 255) / 256 * 256;
     bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + in_bytes);
+    // whole 2 x 2 tiles, rows a multiple of 8 pixels: the pooled map falls out of the repack
+    const bool fuse = Z && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && g.W % 8 == 0;
     *err = launch_repack((const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total,
-                         p.Mp, p.KCp, 0, st);
+                         p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
+    *pooled = fuse;
     if (*err != hipSuccess) return true;
     p.in = in; p.wt = wt; p.bias = (const bf16_t *)b; p.out = (bf16_t *)Y;
     *err = run_gather(p, variant, st);
@@ -615,7 +667,7 @@ bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, voi
         hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (u32x4 *)dX, n16);
     }
     *err = launch_repack((const bf16_t *)dY, in, g.N, g.K, g.P * g.Q, base.KCp, (const bf16_t *)W, wt, g.K, g.C,
-                         base.ntaps_total, base.Mp, base.KCp, 1, st);
+                         base.ntaps_total, base.Mp, base.KCp, 1, nullptr, 0, st);
     for (int k = 0; k < ncls && *err == hipSuccess; ++k) {
         cls[k].in = in; cls[k].wt = wt; cls[k].bias = nullptr; cls[k].out = (bf16_t *)dX;
         *err = run_gather(cls[k], variant[k], st);

@@ -224,6 +224,29 @@ def test_weight_gradient_is_reproducible_bit_for_bit():
         assert np.array_equal(first, run_step(spec, t)["dW"])
 
 
+@pytest.mark.parametrize("shape", [(3, 24, 40, 16, 16), (2, 64, 64, 8, 32), (5, 70, 16, 4, 8)])
+def test_pooling_fused_into_the_forward_pass_equals_the_standalone_kernel(shape):
+    """Where the forward pass forms Z on its way (2 x 2 tiles, rows a multiple of 8 pixels),
+    the bits are those of cac_compress."""
+    import torch
+    from gpu_util import upload, workspace
+    from paper_2409_11902_amd import binding as B
+    N, C, K, H, W = shape
+    spec = synth.LayerSpec("fusedpool", N, C, K, H, W, 3, 3, 1, 1, 2, synth.BF16)
+    t = synth.make_inputs(spec, "fusedpool")
+    d = B.desc_from_spec(spec)
+    X, Wt, b = (upload(t[k], spec.dtype) for k in ("X", "W", "b"))
+    Y = torch.empty((N, K, spec.P, spec.Q), dtype=torch.bfloat16, device="cuda:0")
+    Z1 = torch.full((N, C, H // 2, W // 2), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    Z2 = torch.full_like(Z1, float("nan"))
+    B.conv_fwd_and_compress(d, X, Wt, b, Y, Z1, workspace(d, B.OP_FWD_AND_COMPRESS))
+    B.cac_compress(d, X, Z2)
+    torch.cuda.synchronize()
+    assert torch.equal(Z1.view(torch.int16), Z2.view(torch.int16))
+    want = oracle.avgpool(t["X"].astype(np.float64), 2, 2)
+    assert np.abs(Z2.float().cpu().numpy() - want).max() <= np.abs(want).max() * 2.0 ** -8
+
+
 def test_graph_capture_and_side_stream():
     """The three calls enqueue on the caller's stream only and record no memset nodes: captured
     in a HIP graph on a side stream and replayed several times, with eager work and
