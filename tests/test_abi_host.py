@@ -148,3 +148,24 @@ def test_workspace_too_small_is_reported():
         a = ctypes.c_void_p(0x1000)
         assert L.conv_bwd_weight_compressed(ctypes.byref(d), a, a, a, a, need - 1, None) == B.ERR_WORKSPACE_TOO_SMALL
         assert L.conv_bwd_weight_compressed(ctypes.byref(d), a, a, a, None, 0, None) == B.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_every_bf16_layer_of_the_configs_has_an_mfma_weight_gradient_plan():
+    """Host-side planning only: no layer of the stated workloads falls back to the generic
+    kernel, the plan's staging fits the LDS of a CU, and the workspace query covers the
+    partial sums the plan announces."""
+    import re
+    for name, specs in synth.configs().items():
+        for spec in specs:
+            if spec.dtype != synth.BF16:
+                continue
+            d = B.desc_from_spec(spec)
+            plan = B.cac_describe_plan(d, B.OP_BWD_WEIGHT_COMPRESSED)
+            assert plan.startswith("dw_mfma"), (name, spec.name, plan)
+            lds = int(re.search(r"lds=(\d+)B", plan).group(1))
+            partial = int(re.search(r"partial=(\d+)B", plan).group(1))
+            slices, tiles = map(int, re.search(r"slices=(\d+) x (\d+) tiles", plan).groups())
+            assert lds <= 160 * 1024, (name, spec.name, plan)
+            assert B.cac_workspace_size(d, B.OP_BWD_WEIGHT_COMPRESSED) == partial
+            assert (partial == 0) == (slices == 1)
+            assert slices * tiles <= 2048
