@@ -51,6 +51,17 @@ hipError_t launch_fwd_generic(const Geom &g, int dtype, const void *X, const voi
 hipError_t launch_dx_generic(const Geom &g, int dtype, const void *W, const void *dY, void *dX, hipStream_t st);
 hipError_t launch_dw_generic(const Geom &g, int dtype, const void *Z, const void *dY, float *dW, hipStream_t st);
 hipError_t launch_db(const Geom &g, int dtype, const void *dY, float *db, hipStream_t st);
+// Buffer descriptor over a dense tensor of `bytes` bytes (raw, 32-bit elements): loads through
+// it return zero for every dword that does not lie entirely below the size, without touching
+// memory.  The size is rounded up to whole dwords: a tensor with an odd number of 2-byte
+// elements ends in the middle of a dword, which would otherwise read as zero as a whole; the
+// two bytes past the tensor share that aligned dword, so they are mapped (and never used).
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (bytes + 3u) & ~3u, 0x00020000);
+}
+
 size_t cosine_workspace(long n);
 hipError_t launch_cosine(const float *a, const float *b, long n, float *out, void *ws, hipStream_t st);
 

@@ -15,13 +15,7 @@ namespace cac {
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
 constexpr uint32_t kNoLoad = 0x80000000u;
-
-__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
-}
 
 // EPC consecutive elements starting at element e (any alignment the type
 // allows) as floats; elements past the tensor read as zero.

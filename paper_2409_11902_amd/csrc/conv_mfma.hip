@@ -27,15 +27,9 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
 constexpr uint32_t kNoLoad = 0x80000000u;
 constexpr int KC = 32;       // channels staged per pass
 constexpr int KCS = KC + 8;  // LDS elements per patch pixel: 80 bytes, an odd number of 16-byte units
-
-__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
-}
 
 // ---- repacks ---------------------------------------------------------------------
 

@@ -104,12 +104,6 @@ template <int NB, int SG, int PAD, int s> __device__ __forceinline__ bf16x8 make
 // the tensor's size gets zeros back without touching memory and without a branch,
 // so every load of a chunk can be in flight at once (tensors on this path are
 // smaller than 2 GiB; offsets from 2^31 on mean "no load").
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
-}
-
 // Items are read with one 16-byte load each from the dword-aligned address at or below
 // their first element (rows of odd length start on odd elements).
 // The 8 elements themselves.  After an odd start everything moves down by one
