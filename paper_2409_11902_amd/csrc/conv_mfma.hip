@@ -186,10 +186,13 @@ hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, in
     return hipGetLastError();
 }
 
-__global__ void __launch_bounds__(256) zero_fill_kernel(u32x4 *dst, long n16)
+// Clears n bfloat16 elements: whole 16-byte units, then the (up to 7) elements that remain --
+// not a byte past the tensor.
+__global__ void __launch_bounds__(256) zero_fill_kernel(bf16_t *dst, long n)
 {
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i < n16) dst[i] = u32x4{0, 0, 0, 0};
+    const long i = (long)blockIdx.x * 256 + threadIdx.x, n16 = n / 8;
+    if (i < n16) ((u32x4 *)dst)[i] = u32x4{0, 0, 0, 0};
+    if (i < n - n16 * 8) dst[n16 * 8 + i] = (bf16_t)0;
 }
 
 // ---- the gather GEMM ----------------------------------------------------------------
@@ -657,8 +660,8 @@ bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, voi
     // pixels no output pixel's tap reaches (possible when stride > filter) stay zero
     if (empty_class) {
         // (a fill kernel, not a memset node: callers may capture this call in a HIP graph)
-        const long n16 = ((long)g.N * g.C * g.H * g.W * 2 + 15) / 16; // tensor allocations are 16-byte granular
-        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (u32x4 *)dX, n16);
+        const long n = (long)g.N * g.C * g.H * g.W;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n / 8 + 256) / 256)), dim3(256), 0, st, (bf16_t *)dX, n);
     }
     *err = launch_repack((const bf16_t *)dY, in, g.N, g.K, g.P * g.Q, base.KCp, (const bf16_t *)W, wt, g.K, g.C,
                          base.ntaps_total, base.Mp, base.KCp, 1, nullptr, 0, st);

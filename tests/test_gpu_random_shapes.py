@@ -36,7 +36,31 @@ def _random_specs(count, seed):
     return out
 
 
-SPECS = _random_specs(48, seed=20240911)
+def _mfma_leaning_specs(count, seed):
+    """bf16 only, channel counts that fill MFMA tiles, odd maps (odd element counts, ragged pooling
+    tiles), more images: the shapes the tiled kernels see in the workloads, shrunk."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 3, 3]))
+        stride = int(rng.choice([1, 1, 2]))
+        pad = R // 2 if rng.random() < 0.8 else 0
+        H = int(rng.choice([4, 5, 7, 8, 9, 13, 14, 15, 16, 21, 28]))
+        W = H if rng.random() < 0.6 else int(rng.choice([3, 7, 8, 12, 17, 24]))
+        if H + 2 * pad < R or W + 2 * pad < R:
+            continue
+        N = int(rng.integers(1, 18))
+        C = int(rng.choice([32, 33, 64, 65, 96, 128]))
+        K = int(rng.choice([32, 63, 64, 96, 128, 160]))
+        k = int(rng.choice([1, 2, 2, 4]))
+        if N * C * K * H * W * R * R > 1.2e9:
+            continue
+        out.append(synth.LayerSpec(f"mf{len(out)} N{N} C{C} K{K} {H}x{W} R{R} s{stride} p{pad} k{k}",
+                                   N, C, K, H, W, R, R, stride, pad, k, synth.BF16))
+    return out
+
+
+SPECS = _random_specs(48, seed=20240911) + _mfma_leaning_specs(40, seed=7)
 
 
 @pytest.mark.parametrize("spec", SPECS, ids=[s.name for s in SPECS])
