@@ -68,3 +68,68 @@ def test_random_shape(spec):
     from gpu_util import run_step
     t = synth.make_inputs(spec, "random_shapes")
     _check_step(spec, t, run_step(spec, t))
+
+
+def _anisotropic_cases(count, seed):
+    """Descriptors the square LayerSpec shorthand cannot express: R != S, strides, paddings and
+    pooling factors that differ per axis, with and without bias."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    out = []
+    while len(out) < count:
+        R, S = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        ph, pw = int(rng.integers(0, R)), int(rng.integers(0, S))
+        H, W = int(rng.integers(1, 25)), int(rng.integers(1, 25))
+        if H + 2 * ph < R or W + 2 * pw < S:
+            continue
+        kh, kw = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 8]))
+        N, C, K = int(rng.integers(1, 6)), int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        dtype = synth.BF16 if rng.random() < 0.5 else synth.F32
+        out.append(dict(N=N, C=C, K=K, H=H, W=W, R=R, S=S, sh=sh, sw=sw, ph=ph, pw=pw, kh=kh, kw=kw, dtype=dtype,
+                        bias=bool(rng.random() < 0.7), seed=int(rng.integers(1 << 30))))
+    return out
+
+
+ANISO = _anisotropic_cases(40, seed=99)
+
+
+@pytest.mark.parametrize("c", ANISO, ids=[f"an{i} " + " ".join(f"{k}{v}" for k, v in c.items() if k != "seed") for i, c in enumerate(ANISO)])
+def test_random_anisotropic_descriptor(c):
+    import torch
+    import oracle
+    from gpu_util import Guarded, upload, download, workspace
+    from paper_2409_11902_amd import binding as B
+    from test_gpu_parity import TOL
+    from util import rel_l2
+    g = oracle.ConvGeom(c["N"], c["C"], c["K"], c["H"], c["W"], c["R"], c["S"], c["sh"], c["sw"], c["ph"], c["pw"])
+    rng = np.random.Generator(np.random.Philox(key=c["seed"]))
+    dt = c["dtype"]
+    t = dict(X=synth.to_storage(np.maximum(rng.standard_normal((c["N"], c["C"], c["H"], c["W"]), dtype=np.float32), 0), dt),
+             W=synth.to_storage(0.2 * rng.standard_normal((c["K"], c["C"], c["R"], c["S"]), dtype=np.float32), dt),
+             b=synth.to_storage(0.1 * rng.standard_normal((c["K"],), dtype=np.float32), dt),
+             dY=synth.to_storage(rng.standard_normal((c["N"], c["K"], g.P, g.Q), dtype=np.float32), dt))
+    d = B.make_desc(c["N"], c["C"], c["K"], c["H"], c["W"], c["R"], c["S"], c["sh"], c["sw"], c["ph"], c["pw"], c["kh"], c["kw"],
+                    dtype=B.F32 if dt == synth.F32 else B.BF16, has_bias=int(c["bias"]))
+    hp, wp, zb, xb = B.cac_pooled_shape(d)
+    assert (hp, wp) == oracle.pooled_shape(c["H"], c["W"], c["kh"], c["kw"]) and B.cac_out_shape(d) == (g.P, g.Q)
+    td = torch.float32 if dt == synth.F32 else torch.bfloat16
+    X, Wt, b, dY = (upload(t[k], dt) for k in ("X", "W", "b", "dY"))
+    Y, Z = Guarded((c["N"], c["K"], g.P, g.Q), td), Guarded((c["N"], c["C"], hp, wp), td)
+    dW, dX = Guarded((c["K"], c["C"], c["R"], c["S"]), torch.float32), Guarded((c["N"], c["C"], c["H"], c["W"]), td)
+    db = Guarded((c["K"],), torch.float32)
+    B.conv_fwd_and_compress(d, X, Wt, b if c["bias"] else None, Y.t, Z.t, workspace(d, B.OP_FWD_AND_COMPRESS))
+    B.conv_bwd_weight_compressed(d, Z.t, dY, dW.t, workspace(d, B.OP_BWD_WEIGHT_COMPRESSED))
+    B.conv_bwd_data(d, Wt, dY, dX.t, workspace(d, B.OP_BWD_DATA))
+    B.conv_bwd_bias(d, dY, db.t)
+    torch.cuda.synchronize()
+    f = {k: v.astype(np.float64) for k, v in t.items()}
+    Zo = oracle.avgpool(f["X"], c["kh"], c["kw"])
+    want = dict(Y=oracle.conv_fwd(g, f["X"], f["W"], f["b"] if c["bias"] else None), Z=Zo,
+                dW=oracle.conv_dw(g, oracle.inflate(Zo, c["H"], c["W"], c["kh"], c["kw"]), f["dY"]),
+                dX=oracle.conv_dx(g, f["W"], f["dY"]), db=oracle.bias_grad(f["dY"]))
+    got = dict(Y=Y, Z=Z, dW=dW, dX=dX, db=db)
+    for name in want:
+        got[name].check(name)
+        w = want[name]
+        e = rel_l2(download(got[name].t), w) if np.abs(w).max() > 0 else np.abs(download(got[name].t)).max()
+        assert e <= TOL[dt], f"{name}: {e:.3e}"
