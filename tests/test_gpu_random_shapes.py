@@ -60,7 +60,27 @@ def _mfma_leaning_specs(count, seed):
     return out
 
 
-SPECS = _random_specs(48, seed=20240911) + _mfma_leaning_specs(40, seed=7)
+def _workload_like_specs(count, seed):
+    """The workloads' layer shapes with smaller batches: long enough for several chunks per
+    workgroup, several pixel slices and both workgroup shapes of the weight-gradient kernel."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 3, 3, 3]))
+        stride = int(rng.choice([1, 1, 1, 2]))
+        H = int(rng.choice([4, 7, 8, 14, 16, 28, 32, 56]))
+        N = int(rng.choice([8, 12, 16, 24, 32]))
+        C = int(rng.choice([64, 128, 256]))
+        K = int(rng.choice([64, 128, 256]))
+        k = int(rng.choice([1, 2, 2, 2, 4]))
+        if N * C * K * H * H * R * R > 2.5e9 or N * C * H * H > 4e6:
+            continue
+        out.append(synth.LayerSpec(f"wl{len(out)} N{N} C{C} K{K} {H}x{H} R{R} s{stride} k{k}",
+                                   N, C, K, H, H, R, R, stride, R // 2, k, synth.BF16))
+    return out
+
+
+SPECS = _random_specs(48, seed=20240911) + _mfma_leaning_specs(40, seed=7) + _workload_like_specs(24, seed=3)
 
 
 @pytest.mark.parametrize("spec", SPECS, ids=[s.name for s in SPECS])
