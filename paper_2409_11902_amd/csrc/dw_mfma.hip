@@ -201,7 +201,7 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         const uint32_t dy_ni = fdiv(dy_rho, p.m_pr), dy_pr = dy_rho - dy_ni * p.PR;
         const bool dy_write = dyj < (uint32_t)p.rowitems;         // lanes past the row's items idle
         const bool dy_real = dy_write && dy_rho < (uint32_t)p.LR; // the spare row stays zero
-        const u32x4 dy_mask = mask8(p.Q - (int)dy_sg * 8);
+        u32x4 dy_mask, z_mask, rag[2][2]; // (filled after the first loads are on their way)
         const uint32_t dy_rel = ((dy_ni * p.K + dyo) * p.P + dy_pr) * p.Q + dy_sg * 8;
         const uint32_t dy_opp = (uint32_t)NT >> p.ldy_log2;       // output channels per pass
         const uint32_t dy_gstep = dy_opp * p.P * p.Q;
@@ -212,7 +212,6 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         const uint32_t z_row = fdiv(zj, p.m_zv), z_zv = zj - z_row * p.ZV;
         const uint32_t z_ni = fdiv(z_row, p.m_nz), z_sl = z_row - z_ni * p.NZ;
         const bool z_write = zj < (uint32_t)p.citems;
-        const u32x4 z_mask = mask8(p.Wp - (int)z_zv * 8);
         const uint32_t z_rel = ((z_ni * p.C + zc) * p.Hp + z_sl) * p.Wp + z_zv * 8;
         const uint32_t z_cpp = (uint32_t)NT >> p.lpc_log2;        // input channels per pass
         const uint32_t z_gstep = z_cpp * p.Hp * p.Wp;
@@ -269,13 +268,6 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                 rz[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_z, (e & ~1u) * 2u, 0, 0);
             }
         };
-        // masks of the ragged case for the two blocks an item expands to when f_log2 <= 1
-        u32x4 rag[2][2];
-#pragma unroll
-        for (int ph = 0; ph < 2; ++ph)
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                rag[ph][h] = mask8((p.W - ph + SG - 1) / SG - (int)(z_zv << (3 + max(f_log2, 0))) - 8 * h);
         const int cw = __builtin_amdgcn_readfirstlane(tid >> 6); // index among the copy waves
         // ---- registers -> LDS buffer at element offset `base` (with the horizontal inflation)
         auto stage = [&](int ci, uint32_t base, const u32x4 (&rdy)[kMaxDy], const u32x4 (&rz)[kMaxZ]) {
@@ -397,6 +389,15 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         // before its register is reused and never has to drain the other set's loads.
         fetch(ci_begin, true, dyA, zA); // (every workgroup has at least one chunk)
         fetch(ci_begin + 1, ci_begin + 1 < ci_end, dyB, zB);
+        // what only the staging needs: the masks that cut an item at the end of its row, and,
+        // for the ragged case, the two blocks an item expands to when f_log2 <= 1
+        dy_mask = mask8(p.Q - (int)dy_sg * 8);
+        z_mask = mask8(p.Wp - (int)z_zv * 8);
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                rag[ph][h] = mask8((p.W - ph + SG - 1) / SG - (int)(z_zv << (3 + max(f_log2, 0))) - 8 * h);
         zero_fill(); // in the shadow of the first loads
         __syncthreads();
         stage(ci_begin, base0, dyA, zA);
