@@ -34,7 +34,6 @@ struct DwMfmaPlan {
     unsigned grid, threads;
     size_t partial_bytes;
     int variant;        // index into the kernel table
-    long tile_elems;    // accumulator elements per workgroup (for the reduction)
 };
 
 // False when the geometry is not covered (the caller then uses the generic kernel).

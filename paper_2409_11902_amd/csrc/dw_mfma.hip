@@ -654,8 +654,9 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                         if (jq * KS / 4 != ks) red[(ks * G + ((mi * NI + ni) * T + t) * 4 + jq) * 64] = CAC_GROUP(mi, ni, t, jq);
         __syncthreads();
     }
-    // partial sums in fragment order: [slice][tile][wm, wn][g][lane][j%4]
-    f32x4 *part = (f32x4 *)p.out + (((long)slice * ntiles + tile) * (WM * WN) + wn * WM + wm) * (G * 64) + lane;
+    // Output: dW itself (one slice), or this slice's partial sums in the workspace, in the same
+    // [o][c][tap] order, so that the sum over the slices is a plain stream.
+    float *out = p.direct ? p.out : p.out + (long)slice * p.K * p.C * T;
     const bool inside = o0 + TILE_O <= p.K && c0 + TILE_C <= p.C; // no edge of dW crosses the tile
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
@@ -674,15 +675,10 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                             if (k2 != ks) v[t] += red[(k2 * G + ((mi * NI + ni) * T + t) * 4 + jq) * 64];
                     }
                 }
-                if (!p.direct) {
-#pragma unroll
-                    for (int t = 0; t < T; ++t) part[(((mi * NI + ni) * T + t) * 4 + jq) * 64] = v[t];
-                    continue;
-                }
-                // dW itself: the T taps of one (o, c) are consecutive floats
+                // the T taps of one (o, c) are consecutive floats
                 const int c = c0 + (wn * NI + ni) * 32 + l32;
                 const int ob = o0 + (wm * MI + mi) * 32 + 8 * jq + 4 * half;
-                float *dst = p.out + ((long)ob * p.C + c) * T;
+                float *dst = out + ((long)ob * p.C + c) * T;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (inside || (ob + e < p.K && c < p.C)) {
@@ -701,37 +697,30 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
 #undef CAC_GROUP
 }
 
-// Sums the slices' partial tiles in slice order and writes dW in its own layout.
-// A block of 256 threads owns 256/SY groups of 4 consecutive partial elements
-// (one 16-byte load per slice and thread); its SY thread rows take every SY-th
-// slice each and are combined through LDS in a fixed order, so the result does
-// not depend on scheduling.
-struct ReduceShape {
-    int nslices, tiles_o, tiles_c, T, K, C, MI, NI, WM, WN;
-};
-template <int SY>
-__global__ void __launch_bounds__(256) dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW, ReduceShape s)
+// dW = sum over the slices of their partial sums, in slice order.  A block of 256 threads owns
+// 256/SY vectors of V floats; its SY thread rows take every SY-th slice each and are combined
+// through LDS in a fixed order, so the result does not depend on scheduling.
+template <int SY, int V>
+__global__ void __launch_bounds__(256) dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW, long total, int nslices)
 {
-    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    typedef float vec __attribute__((ext_vector_type(V)));
     constexpr int CX = 256 / SY;
-    __shared__ f32x4 red[SY > 1 ? SY : 1][CX];
+    __shared__ vec red[SY > 1 ? SY : 1][CX];
     const int cx = threadIdx.x % CX, sy = threadIdx.x / CX;
-    const long per_tile = (long)s.WM * s.WN * s.MI * s.NI * s.T * 16 * 64;
-    const long per_slice4 = per_tile * s.tiles_o * s.tiles_c / 4;
-    const long col = (long)blockIdx.x * CX + cx; // index of the group of 4 elements
-    if (col >= per_slice4) return;                // (whole blocks only: per_slice4 is a multiple of 256)
-    const f32x4 *src = (const f32x4 *)part + col;
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    const long nvec = total / V, col = (long)blockIdx.x * CX + cx;
+    const bool valid = col < nvec;
+    const vec *src = (const vec *)part + (valid ? col : 0);
+    vec sum = 0.f;
     int sl = sy;
-    for (; sl + 3 * SY < s.nslices; sl += 4 * SY) {
-        const f32x4 a = src[(long)sl * per_slice4], b = src[(long)(sl + SY) * per_slice4];
-        const f32x4 c = src[(long)(sl + 2 * SY) * per_slice4], d = src[(long)(sl + 3 * SY) * per_slice4];
+    for (; sl + 3 * SY < nslices; sl += 4 * SY) {
+        const vec a = src[(long)sl * nvec], b = src[(long)(sl + SY) * nvec];
+        const vec c = src[(long)(sl + 2 * SY) * nvec], d = src[(long)(sl + 3 * SY) * nvec];
         sum += a;
         sum += b;
         sum += c;
         sum += d;
     }
-    for (; sl < s.nslices; sl += SY) sum += src[(long)sl * per_slice4];
+    for (; sl < nslices; sl += SY) sum += src[(long)sl * nvec];
     if (SY > 1) {
         red[sy][cx] = sum;
         __syncthreads();
@@ -739,76 +728,7 @@ __global__ void __launch_bounds__(256) dw_reduce_kernel(const float *__restrict_
 #pragma unroll
         for (int k = 1; k < SY; ++k) sum += red[k][cx];
     }
-    // col -> [tile][wave][mi][ni][tap][j/4][lane]; the 4 elements are registers 4*(j/4)..+3
-    const int lane = col & 63;
-    long t1 = col >> 6;
-    const int jq = t1 & 3;
-    t1 >>= 2;
-    const int tap = t1 % s.T;
-    t1 /= s.T;
-    const int ni = t1 % s.NI;
-    t1 /= s.NI;
-    const int mi = t1 % s.MI;
-    t1 /= s.MI;
-    const int wave = t1 % (s.WM * s.WN);
-    const int tile = t1 / (s.WM * s.WN);
-    const int wm = wave % s.WM, wn = wave / s.WM;
-    const int ot = tile / s.tiles_c, ct = tile - ot * s.tiles_c;
-    const int c = (ct * s.WN + wn) * s.NI * 32 + ni * 32 + (lane & 31);
-    if (c >= s.C) return;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        // accumulator register j = 4*jq + e holds row 8*(j/4) + 4*(lane/32) + j%4
-        const int o = (ot * s.WM + wm) * s.MI * 32 + mi * 32 + 8 * jq + 4 * (lane >> 5) + e;
-        if (o < s.K) dW[((long)o * s.C + c) * s.T + tap] = sum[e];
-    }
-}
-
-// The same reduction for few slices and large outputs: a block owns one wave's
-// 32 (o) x 32 (c) x taps block, sums it over the slices (slice order), transposes
-// it through LDS and writes whole rows of dW (32*T consecutive floats) instead
-// of single floats.
-template <int T>
-__global__ void __launch_bounds__(256) dw_reduce_tile_kernel(const float *__restrict__ part, float *__restrict__ dW, ReduceShape s)
-{
-    typedef __attribute__((ext_vector_type(4))) float f32x4;
-    __shared__ float red[32][32 * T + 1];
-    const int t = threadIdx.x, lane = t & 63, jq = t >> 6;
-    const long per_tile = (long)s.WM * s.WN * s.MI * s.NI * T * 16 * 64;
-    const long per_slice4 = per_tile * s.tiles_o * s.tiles_c / 4;
-    const f32x4 *src = (const f32x4 *)part + (long)blockIdx.x * (T * 256) + t;
-    f32x4 sum[T];
-#pragma unroll
-    for (int k = 0; k < T; ++k) sum[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int sl = 0; sl < s.nslices; ++sl) {
-        f32x4 v[T];
-#pragma unroll
-        for (int k = 0; k < T; ++k) v[k] = src[(long)sl * per_slice4 + k * 256];
-#pragma unroll
-        for (int k = 0; k < T; ++k) sum[k] += v[k];
-    }
-    // register j = 4*jq + e of lane l holds row 8*jq + 4*(l/32) + e, column l%32
-#pragma unroll
-    for (int k = 0; k < T; ++k)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) red[8 * jq + 4 * (lane >> 5) + e][(lane & 31) * T + k] = sum[k][e];
-    __syncthreads();
-    // block index -> [tile][wave][mi][ni]
-    int b = blockIdx.x;
-    const int ni = b % s.NI;
-    b /= s.NI;
-    const int mi = b % s.MI;
-    b /= s.MI;
-    const int wave = b % (s.WM * s.WN);
-    const int tile = b / (s.WM * s.WN);
-    const int wm = wave % s.WM, wn = wave / s.WM;
-    const int ot = tile / s.tiles_c, ct = tile - ot * s.tiles_c;
-    const int o0 = (ot * s.WM + wm) * s.MI * 32 + mi * 32, c0 = (ct * s.WN + wn) * s.NI * 32 + ni * 32;
-    const int ncols = min(32, s.C - c0) * T; // floats of a row that exist
-    for (int idx = t; idx < 32 * 32 * T; idx += 256) {
-        const int row = idx / (32 * T), col = idx - row * (32 * T);
-        if (o0 + row < s.K && col < ncols) dW[((long)(o0 + row) * s.C + c0) * T + col] = red[row][col];
-    }
+    if (valid) ((vec *)dW)[col] = sum;
 }
 
 uint32_t magic_of(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
@@ -970,8 +890,7 @@ bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
     p.direct = p.nslices == 1;
     plan->grid = ((p.total_wg + 7) / 8) * 8;
     plan->threads = NT;
-    plan->tile_elems = (long)tile_o * tile_c * T;
-    plan->partial_bytes = p.direct ? 0 : (size_t)p.nslices * ntiles * plan->tile_elems * sizeof(float);
+    plan->partial_bytes = p.direct ? 0 : (size_t)p.nslices * g.K * g.C * T * sizeof(float);
     plan->variant = vi;
     return true;
 }
@@ -1024,22 +943,22 @@ hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY,
     const Variant &var = kVariants[plan.variant];
     hipError_t e = var.launch(p, dim3(plan.grid), st);
     if (e != hipSuccess || p.direct) return e;
-    ReduceShape rs{p.nslices, p.tiles_o, p.tiles_c, var.R * var.R, p.K, p.C, var.MI, var.NI, var.WM, var.WN};
-    const long per_slice = plan.tile_elems * p.tiles_o * p.tiles_c;
-    // thread rows over the slices: enough of them to keep a few hundred thousand loads in flight
-    const long cols = per_slice / 4;
-    const unsigned blocks = (unsigned)(per_slice / (1024 * rs.T)); // of the whole-row kernel
-    if (p.nslices <= 8 && blocks >= 256) {
-        if (rs.T == 9)
-            hipLaunchKernelGGL(dw_reduce_tile_kernel<9>, dim3(blocks), dim3(256), 0, st, (const float *)ws, dW, rs);
-        else
-            hipLaunchKernelGGL(dw_reduce_tile_kernel<1>, dim3(blocks), dim3(256), 0, st, (const float *)ws, dW, rs);
-    } else if (p.nslices <= 8 || cols >= (1 << 18))
-        hipLaunchKernelGGL(dw_reduce_kernel<1>, dim3((unsigned)(cols / 256)), dim3(256), 0, st, (const float *)ws, dW, rs);
-    else if (p.nslices <= 32 || cols >= (1 << 16))
-        hipLaunchKernelGGL(dw_reduce_kernel<4>, dim3((unsigned)(cols / 64)), dim3(256), 0, st, (const float *)ws, dW, rs);
-    else
-        hipLaunchKernelGGL(dw_reduce_kernel<16>, dim3((unsigned)(cols / 16)), dim3(256), 0, st, (const float *)ws, dW, rs);
+    const long total = (long)p.K * p.C * var.R * var.R;
+    // vectors of 4 floats when a slice is a whole number of them (every slice then starts aligned);
+    // thread rows over the slices when there are many of them
+#define CAC_REDUCE(SY, V)                                                                                              \
+    hipLaunchKernelGGL((dw_reduce_kernel<SY, V>), dim3((unsigned)((total / V + 256 / SY - 1) / (256 / SY))), dim3(256), 0, st, \
+                       (const float *)ws, dW, total, p.nslices)
+    if (total % 4 == 0) {
+        if (p.nslices >= 32) CAC_REDUCE(16, 4);
+        else if (p.nslices >= 8) CAC_REDUCE(4, 4);
+        else CAC_REDUCE(1, 4);
+    } else {
+        if (p.nslices >= 32) CAC_REDUCE(16, 1);
+        else if (p.nslices >= 8) CAC_REDUCE(4, 1);
+        else CAC_REDUCE(1, 1);
+    }
+#undef CAC_REDUCE
     return hipGetLastError();
 }
 
