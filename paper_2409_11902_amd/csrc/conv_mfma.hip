@@ -10,13 +10,10 @@
 //   data gradient, s=2: one launch per output parity class (a0, b0) with the
 //                       taps whose (a0 + pad - r) and (b0 + pad - s) are even.
 // The reduction index kc must be contiguous per pixel for the MFMA operand
-// layout, hence a channels-last repack of the input (workspace) and a
-// [tap][m][kc] repack of the filter, both padded with zeros to multiples of 16.
-//
-// Workgroup: 4 waves as WM x WN; a wave owns 64 (m) x 32*NI (pixels).  The input
-// patch of the pixel tile (with its halo, KC channels at a time) is staged in
-// LDS once and serves every tap; filter fragments come straight from global
-// memory (small, cache resident), fetched one step ahead.
+// layout, hence a channels-last repack of the input (workspace) and a repack of
+// the filter into MFMA fragment order, both padded with zeros to multiples of 16
+// (one launch, repack_kernel; the forward pass forms the 2 x 2 pooled map there
+// too where the tiles are whole).  The GEMM itself is conv_gather_kernel below.
 #include "common.h"
 #include "conv_mfma.h"
 

@@ -7,9 +7,11 @@
 //                                             replication)
 //
 // GEMM view: M = output channels o, N = (input channel c, filter tap), K = pixels.
-// A workgroup of WM x WN waves owns a (32*MI*WM) x (32*NI*WN) x all-taps tile and
-// a slice of the pixels; each wave MI x NI x taps accumulator blocks of 32x32,
-// one wave per SIMD.
+// A workgroup owns a (32*MI*WM) x (32*NI*WN) x all-taps tile and a slice of the
+// pixels.  It has WM*WN*KS MFMA waves -- each holding MI x NI x taps accumulator
+// blocks of 32x32; the KS waves that share a block split the rows of every chunk
+// and add up through LDS at the end -- and as many copy waves, which bring the
+// operands from global memory into LDS (one MFMA and one copy wave per SIMD).
 //
 // The pixel sum is re-indexed by the xhat column instead of the output column:
 // with s - PAD = SG*a_s + b_s (0 <= b_s < SG),
