@@ -179,6 +179,10 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
                  plan.variant, p.tile_o, p.tile_c, p.NBI, p.PR, p.LR, p.LRpad, p.SEGS, p.NZ, p.XW, p.rowitems, p.citems, p.dy_passes,
                  p.z_passes, p.lds_bytes, p.nchunks, p.nslices, p.tiles_o * p.tiles_c, plan.grid,
                  plan.partial_bytes);
+    } else if ((op == CAC_OP_FWD_AND_COMPRESS || op == CAC_OP_BWD_DATA) &&
+               describe_conv_mfma(g, d->dtype, op == CAC_OP_BWD_DATA, buf, buf_len)) {
+    } else if (op == CAC_OP_COMPRESS || op == CAC_OP_GRAD_COSINE) {
+        snprintf(buf, buf_len, "streaming kernel");
     } else {
         snprintf(buf, buf_len, "generic kernel");
     }

@@ -9,6 +9,7 @@ struct GatherParams {
     const bf16_t *wt;   // [ntaps_total][KCp/16][Mp/32][64][8], MFMA fragment order
     const bf16_t *bias; // [M] or null
     bf16_t *out;        // [N][M][Hout][Wout]
+    float *part;        // [ksplit][N][M][Hout*Wout] float sums when the channels are shared out, else null
     int N, M, Mp, KCp;
     int Hin, Win, Hout, Wout;
     int Hc, Wc;         // grid of output pixels of this launch: (h, w) = (i*os + a0, j*os + b0)
@@ -19,10 +20,13 @@ struct GatherParams {
     int PH, PWd;        // input patch of one image staged per workgroup (rows, columns)
     int IPT, patch_px;  // images per pixel tile; patch pixels of the whole tile
     int tiles_per_img, ngrp, gpw, nkb; // tiles per image; image groups; groups per workgroup; channel blocks
-    uint32_t m_wc, m_ppi, m_pwd, m_nkb, m_img; // division magics of Wc, Hc*Wc, PWd, nkb, PH*PWd
+    int ksplit, kbs;    // workgroups sharing one tile's channel blocks (grid z); channel blocks of each
+    uint32_t m_wc, m_ppi, m_pwd, m_kbs, m_img; // division magics of Wc, Hc*Wc, PWd, kbs, PH*PWd
 };
 
 size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad);
+// Text description of the launch shape(s) chosen; false when the geometry is not covered.
+bool describe_conv_mfma(const Geom &g, int dtype, bool data_grad, char *buf, size_t len);
 bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *Z, void *ws,
                      hipStream_t st, hipError_t *err, bool *pooled);
 bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,

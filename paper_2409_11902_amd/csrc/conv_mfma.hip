@@ -14,6 +14,9 @@
 // the filter into MFMA fragment order, both padded with zeros to multiples of 16
 // (one launch, repack_kernel; the forward pass forms the 2 x 2 pooled map there
 // too where the tiles are whole).  The GEMM itself is conv_gather_kernel below.
+#include <stdio.h>
+#include <stdlib.h>
+
 #include "common.h"
 #include "conv_mfma.h"
 
@@ -211,7 +214,7 @@ constexpr uint32_t kNoElem = 0x40000000u;
 // TR: the accumulators hold the transposed tile (lanes = output channels, registers = pixels):
 // a lane then owns runs of 4 consecutive pixels and writes them as one 8-byte store.  Used when
 // consecutive pixels of the launch are consecutive and 8-byte aligned in memory.
-template <int NI, int WM, int WN, bool TR>
+template <int NI, int WM, int WN, bool TR, bool DEEP>
 __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 {
     constexpr int MI = 2;
@@ -222,7 +225,8 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int tau = blockIdx.x % p.tiles_per_img, run = blockIdx.x / p.tiles_per_img;
     const int g_begin = run * p.gpw, g_end = min(g_begin + p.gpw, p.ngrp);
-    const int nstages = (g_end - g_begin) * p.nkb;
+    const int kb0 = blockIdx.z * p.kbs;             // this workgroup's share of the channel blocks
+    const int nstages = (g_end - g_begin) * p.kbs;
     const int ppi = p.Hc * p.Wc;
     const int pix0 = p.IPT > 1 ? 0 : tau * PT;      // first class-grid pixel of the tile
     const int i0 = fdiv(pix0, p.m_wc);               // its row
@@ -251,7 +255,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         // global -> registers for stage s (dead stages load nothing but are issued all the same:
         // the number of loads in flight is then the same on every path)
         auto fetch = [&](int s, u32x4 (&r)[kMaxItems]) {
-            const int u = fdiv(s, p.m_nkb), kb = s - u * p.nkb;
+            const int u = fdiv(s, p.m_kbs), kb = kb0 + s - u * p.kbs;
             const int n_base = (g_begin + u) * p.IPT;
             const uint32_t sbase = (uint32_t)n_base * p.Hin * p.Win * p.KCp + kb * KC;
             const bool lane_ok = s < nstages && kb * KC + v8 < p.KCp;
@@ -345,10 +349,29 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     // operands (LDS) are requested one step ahead.
     static_assert(KC / 16 == 2, "the prefetch distance below is one tap");
     u32x4 wcur[MI], wnxt[MI], wnn[MI];
+    // DEEP (nine taps): a ring of D steps of fragments instead, enough to cover a miss in the
+    // vector cache at full MFMA rate.  A stage is 18 steps, a multiple of D, so that step q of
+    // every stage uses ring slot q % D and, once the steps are unrolled, every slot is a fixed
+    // register.  The uniform part of a fragment's address goes into the load's scalar offset.
+    constexpr int D = 6, STEPS = 9 * (KC / 16);
+    static_assert(STEPS % D == 0, "ring slots must not move from stage to stage");
+    u32x4 wr[DEEP ? D : 1][MI];
+    uint32_t wl[9];
+    if constexpr (DEEP) {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        wcur[mi] = wfrag(wofs[0], 0, mi);
-        wnxt[mi] = wfrag(wofs[0], 1, mi);
+        for (int t = 0; t < 9; ++t) wl[t] = wlane + wofs[t];
+#pragma unroll
+        for (int q = 0; q < D; ++q)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                wr[q][mi] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rs_w, wl[q >> 1], (uint32_t)((kb0 * (KC / 16) + (q & 1)) * mblks + mi) * kFrag, 0);
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            wcur[mi] = wfrag(wofs[0], kb0 * (KC / 16), mi);
+            wnxt[mi] = wfrag(wofs[0], kb0 * (KC / 16) + 1, mi);
+        }
     }
 
     __syncthreads(); // buffer 0 holds stage 0
@@ -356,17 +379,66 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     for (int s = 0; s < nstages; ++s) {
         if (wave_live) {
             const uint32_t buf = (s & 1) ? buf_bytes : 0u;
-            const int kb_next = kb + 1 == p.nkb ? 0 : kb + 1;
+            const int kb_next = kb + 1 == p.kbs ? 0 : kb + 1;
             u32x4 bcur[NI], bnxt[NI];
+            if constexpr (!DEEP) {
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) bcur[ni] = *(const u32x4 *)(smem + buf + pbase[ni] + toff[0]);
+                for (int ni = 0; ni < NI; ++ni) bcur[ni] = *(const u32x4 *)(smem + buf + pbase[ni] + toff[0]);
+            }
+            if constexpr (DEEP) {
+                const uint32_t so_cur = (uint32_t)((kb0 + kb) * (KC / 16) * mblks) * kFrag;
+                const uint32_t so_nxt = (uint32_t)((kb0 + kb_next) * (KC / 16) * mblks) * kFrag;
+                // pixel operands: a ring of DB steps in registers of their own (a copy from a
+                // "next" to a "current" set lets the compiler merge the two and issue the LDS read
+                // only after the current value's last use, a fraction of a step ahead)
+                constexpr int DB = 3;
+                static_assert(STEPS % DB == 0, "ring slots must not move from stage to stage");
+                u32x4 bq[DB][NI];
+                auto pixels = [&](int q, int ni) { return *(const u32x4 *)(smem + buf + pbase[ni] + toff[q >> 1] + 32 * (q & 1)); };
+#pragma unroll
+                for (int q = 0; q < DB - 1; ++q)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) bq[q][ni] = pixels(q, ni);
+#pragma unroll
+                for (int q = 0; q < STEPS; ++q) {
+                    // pixels of step q + DB - 1 (nothing past the stage's last step: the other
+                    // buffer is not ready yet)
+                    if (q + DB - 1 < STEPS) {
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) bq[(q + DB - 1) % DB][ni] = pixels(q + DB - 1, ni);
+                    }
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int mi = 0; mi < MI; ++mi) {
+                            union { u32x4 u; bf16x8 v; } af, bf;
+                            af.u = wr[q % D][mi];
+                            bf.u = bq[q % DB][ni];
+                            acc[mi][ni] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf.v, af.v, acc[mi][ni], 0, 0, 0)
+                                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[mi][ni], 0, 0, 0);
+                        }
+                    // refill the slot with the fragments of step q + D (of this stage or the next;
+                    // after the last stage: of the first again, never used)
+                    const int q2 = q + D < STEPS ? q + D : q + D - STEPS;
+                    const uint32_t so = (q + D < STEPS ? so_cur : so_nxt) + (uint32_t)((q2 & 1) * mblks) * kFrag;
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+                        wr[q % D][mi] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, wl[q2 >> 1], so + mi * kFrag, 0);
+                    // Pin the order LDS reads, MFMAs, refill, and keep the instruction scheduler from
+                    // moving anything to another step (it would sink the loads towards their uses).
+                    if (q + DB - 1 < STEPS) __builtin_amdgcn_sched_group_barrier(0x100, NI, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, MI, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else
 #pragma unroll
             for (int t = 0; t < 9; ++t) {
                 if (t >= p.ntaps) break;
                 const bool last = t + 1 >= p.ntaps;
                 const uint32_t wo_n = last ? wofs[0] : wofs[t + 1 < 9 ? t + 1 : 0];
                 const uint32_t to_n = toff[t + 1 < 9 ? t + 1 : 0];
-                const int kblk_n = (last ? kb_next : kb) * (KC / 16);
+                const int kblk_n = (kb0 + (last ? kb_next : kb)) * (KC / 16);
 #pragma unroll
                 for (int kk = 0; kk < KC / 16; ++kk) {
 #pragma unroll
@@ -399,7 +471,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                     for (int ni = 0; ni < NI; ++ni) bcur[ni] = bnxt[ni];
                 }
             }
-            if (kb == p.nkb - 1) {
+            if (kb == p.kbs - 1) {
                 // ---- epilogue of the unit: bias, bfloat16, NCHW
                 const int n_base = (g_begin + unit) * p.IPT;
                 if constexpr (TR) {
@@ -423,6 +495,12 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                                 const int n = n_base + g;
                                 if (m < p.M && px < ppi && g < p.IPT && n < p.N) {
                                     const f32x16 &a = acc[mi][ni];
+                                    if (p.part) { // a share of the channels: float sums, finished by gather_finish_kernel
+                                        typedef __attribute__((ext_vector_type(4))) float f32x4;
+                                        *(f32x4 *)(p.part + (((long)blockIdx.z * p.N + n) * p.M + m) * ppi + px) =
+                                            f32x4{a[4 * jq], a[4 * jq + 1], a[4 * jq + 2], a[4 * jq + 3]};
+                                        continue;
+                                    }
                                     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
                                     const u32x2 v = {(uint32_t)f32_to_bf16(a[4 * jq] + bias) | ((uint32_t)f32_to_bf16(a[4 * jq + 1] + bias) << 16),
                                                      (uint32_t)f32_to_bf16(a[4 * jq + 2] + bias) | ((uint32_t)f32_to_bf16(a[4 * jq + 3] + bias) << 16)};
@@ -457,7 +535,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                 }
             }
         }
-        if (++kb == p.nkb) {
+        if (++kb == p.kbs) {
             kb = 0;
             ++unit;
         }
@@ -465,9 +543,26 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     }
 }
 
-template <int NI, int WM, int WN, bool TR> hipError_t launch_gather_tr(const GatherParams &p, hipStream_t st)
+// out = bfloat16(bias + sum over the channel shares of their float sums), 4 pixels per thread.
+__global__ void __launch_bounds__(256) gather_finish_kernel(const float *__restrict__ part, const bf16_t *__restrict__ bias,
+                                                            bf16_t *__restrict__ out, long quads, int nsplit, int ppi, int M)
 {
-    auto kern = conv_gather_kernel<NI, WM, WN, TR>;
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    const long q = (long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= quads) return;
+    const f32x4 *src = (const f32x4 *)part + q;
+    f32x4 sum = src[0];
+    for (int k = 1; k < nsplit; ++k) sum += src[k * quads];
+    if (bias) sum += bf16_to_f32(bias[(int)((q * 4 / ppi) % M)]);
+    const u32x2 v = {(uint32_t)f32_to_bf16(sum[0]) | ((uint32_t)f32_to_bf16(sum[1]) << 16),
+                     (uint32_t)f32_to_bf16(sum[2]) | ((uint32_t)f32_to_bf16(sum[3]) << 16)};
+    *((u32x2 *)out + q) = v;
+}
+
+template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_shape(const GatherParams &p, hipStream_t st)
+{
+    auto kern = conv_gather_kernel<NI, WM, WN, TR, DEEP>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -475,8 +570,13 @@ template <int NI, int WM, int WN, bool TR> hipError_t launch_gather_tr(const Gat
         attr_set = true;
     }
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw;
-    dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM);
+    dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM, p.ksplit);
     hipLaunchKernelGGL(kern, grid, dim3(512), (size_t)2 * p.patch_px * KCS * 2, st, p);
+    if (p.ksplit > 1) {
+        const long quads = (long)p.N * p.M * p.Hc * p.Wc / 4;
+        hipLaunchKernelGGL(gather_finish_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, (const float *)p.part,
+                           p.bias, p.out, quads, p.ksplit, p.Hc * p.Wc, p.M);
+    }
     return hipGetLastError();
 }
 
@@ -485,12 +585,21 @@ template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p
     // runs of 4 pixels are contiguous and 8-byte aligned: the class grid is the whole output
     // plane and a plane is a multiple of 4 pixels
     const bool packed = p.os == 1 && p.Hc == p.Hout && p.Wc == p.Wout && (p.Hc * p.Wc) % 4 == 0;
-    return packed ? launch_gather_tr<NI, WM, WN, true>(p, st) : launch_gather_tr<NI, WM, WN, false>(p, st);
+    if (p.ntaps == 9) return packed ? launch_gather_shape<NI, WM, WN, true, true>(p, st) : launch_gather_shape<NI, WM, WN, false, true>(p, st);
+    return packed ? launch_gather_shape<NI, WM, WN, true, false>(p, st) : launch_gather_shape<NI, WM, WN, false, false>(p, st);
 }
 
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Chooses the workgroup shape and fills the tiling; false if no shape fits.
+//
+// Candidates: waves along m (wm) x pixel blocks per wave (ni), and, where the output is written
+// in whole planes, the number of workgroups that share a tile's channel blocks (their float sums
+// go to the workspace and gather_finish_kernel adds them up).  Each is priced with a rough model
+// in clock cycles: a step (one tap, 16 channels) costs a wave 32 cycles per MFMA but at least the
+// time the CU's vector cache needs for the four waves' filter fragments; a workgroup pays a fixed
+// start-up and epilogue; the chip runs 256 workgroups at a time; all filter and input bytes have
+// to come through L2; shared-out channels cost a second kernel and the traffic of the sums.
 bool shape_gather(GatherParams &p, int *variant)
 {
     p.dhmin = p.dwmin = 1 << 30;
@@ -501,13 +610,19 @@ bool shape_gather(GatherParams &p, int *variant)
     }
     p.PWd = (p.Wc - 1) * p.is + (dwmax - p.dwmin) + 1;
     p.nkb = (p.KCp + KC - 1) / KC;
+    p.part = nullptr;
     const int ppi = p.Hc * p.Wc;
     auto magic = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
-    p.m_wc = magic(p.Wc); p.m_ppi = magic(ppi); p.m_pwd = magic(p.PWd); p.m_nkb = magic(p.nkb);
-    // Candidates: waves along m (wm) x pixel blocks per wave (ni), large tiles first; the first
-    // that fills the chip is taken, else the one with the most workgroups.
+    p.m_wc = magic(p.Wc); p.m_ppi = magic(ppi); p.m_pwd = magic(p.PWd);
+    const bool whole_planes = p.os == 1 && p.Hc == p.Hout && p.Wc == p.Wout && ppi % 4 == 0;
+    const char *force = nullptr;
+    int f_wm = 0, f_ni = 0, f_ks = 0;
+#ifdef CAC_TUNING // development builds: CAC_GATHER_SHAPE="wm,ni,ksplit" overrides the model
+    force = getenv("CAC_GATHER_SHAPE");
+    if (force) sscanf(force, "%d,%d,%d", &f_wm, &f_ni, &f_ks);
+#endif
     GatherParams best{};
-    long best_wgs = -1;
+    double best_cost = 1e300;
     int best_variant = 0;
     for (int wm : {4, 2, 1}) {
         if (wm * 64 > p.Mp && wm > 1) continue;
@@ -529,20 +644,32 @@ bool shape_gather(GatherParams &p, int *variant)
             if ((long)2 * q.patch_px * KCS * 2 > 150 * 1024) continue;
             q.m_img = magic(q.PH * q.PWd);
             q.ngrp = (q.N + q.IPT - 1) / q.IPT;
-            const long wgs1 = (long)q.tiles_per_img * q.ngrp * ((q.Mp / 64 + wm - 1) / wm);
-            // a few units per workgroup (a longer pipeline) as long as every CU still gets a workgroup
-            q.gpw = (int)max(1L, min((long)((8 + q.nkb - 1) / q.nkb), wgs1 / 256));
-            const long wgs = (long)q.tiles_per_img * ((q.ngrp + q.gpw - 1) / q.gpw) * ((q.Mp / 64 + wm - 1) / wm);
-            const int v = (ni == 2 ? 0 : 3) + (wm == 1 ? 0 : wm == 2 ? 1 : 2);
-            if (wgs >= 256) {
-                p = q;
-                *variant = v;
-                return true;
+            const int mtiles = (q.Mp / 64 + wm - 1) / wm;
+            const long wgs1 = (long)q.tiles_per_img * q.ngrp * mtiles;
+            for (int ks = 1; ks <= (whole_planes ? q.nkb : 1); ++ks) {
+                if (q.nkb % ks) continue;
+                if (force && (wm != f_wm || ni != f_ni || ks != f_ks)) continue;
+                q.ksplit = ks;
+                q.kbs = q.nkb / ks;
+                q.m_kbs = magic(q.kbs);
+                // a few units per workgroup (a longer pipeline) as long as every CU still gets a workgroup
+                q.gpw = (int)max(1L, min((long)((8 + q.kbs - 1) / q.kbs), wgs1 * ks / 256));
+                const long runs = (q.ngrp + q.gpw - 1) / q.gpw;
+                const long wgs = (long)q.tiles_per_img * runs * mtiles * ks;
+                const double step = max(64.0 * ni, 128.0) * 1.5;
+                const double t_wg = (double)q.gpw * q.kbs * 2 * q.ntaps * step + 8000.0;
+                const double l2_bytes = (double)wgs * q.gpw * q.kbs * KC * 2.0 * (q.ntaps * 64.0 * wm + q.patch_px);
+                double cost = max((double)((wgs + 255) / 256) * t_wg, l2_bytes / 6000.0 + 8000.0);
+                if (ks > 1) cost += 6000.0 + (double)ks * q.N * q.M * ppi * 8.0 / 2500.0;
+                if (cost < best_cost) {
+                    best_cost = cost;
+                    best = q;
+                    best_variant = (ni == 2 ? 0 : 3) + (wm == 1 ? 0 : wm == 2 ? 1 : 2);
+                }
             }
-            if (wgs > best_wgs) { best_wgs = wgs; best = q; best_variant = v; }
         }
     }
-    if (best_wgs < 0) return false;
+    if (best_cost > 1e299) return false;
     p = best;
     *variant = best_variant;
     return true;
@@ -571,31 +698,11 @@ bool supported(const Geom &g, int dtype)
     return true;
 }
 
-} // namespace
-
-size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad)
+// Forward pass as a gather GEMM: output channels x output pixels, taps (r - ph, s - pw).
+bool plan_fwd(const Geom &g, int dtype, GatherParams &p, int *variant)
 {
-    if (!supported(g, dtype)) return 0;
-    const int RS = g.R * g.S;
-    if (!data_grad) {
-        const size_t in = (size_t)g.N * g.H * g.W * round_up(g.C, 16) * 2;
-        const size_t wt = (size_t)RS * round_up(g.K, 64) * round_up(g.C, 16) * 2;
-        return (in + 255) / 256 * 256 + wt;
-    }
-    const size_t in = (size_t)g.N * g.P * g.Q * round_up(g.K, 16) * 2;
-    const size_t wt = (size_t)RS * round_up(g.C, 64) * round_up(g.K, 16) * 2;
-    return (in + 255) / 256 * 256 + wt;
-}
-
-// Forward: Y = X * W + b.  False when the geometry is not covered.
-// *pooled: Z has been written on the way (the channels-last repack reads X anyway); otherwise
-// the caller runs the compress kernel.
-bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *Z, void *ws,
-                     hipStream_t st, hipError_t *err, bool *pooled)
-{
-    *pooled = false;
     if (!supported(g, dtype)) return false;
-    GatherParams p{};
+    p = GatherParams{};
     p.N = g.N; p.M = g.K; p.Mp = round_up(g.K, 64); p.KCp = round_up(g.C, 16);
     p.Hin = g.H; p.Win = g.W; p.Hout = g.P; p.Wout = g.Q; p.Hc = g.P; p.Wc = g.Q;
     p.os = 1; p.a0 = p.b0 = 0; p.is = g.sh;
@@ -605,34 +712,21 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
             const int t = r * g.S + s;
             p.dh[t] = r - g.ph; p.dw[t] = s - g.pw; p.wtap[t] = t;
         }
-    int variant;
-    if (!shape_gather(p, &variant)) return false;
-    const size_t in_bytes = ((size_t)g.N * g.H * g.W * p.KCp * 2 + 255) / 256 * 256;
-    bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + in_bytes);
-    // whole 2 x 2 tiles, rows a multiple of 8 pixels: the pooled map falls out of the repack
-    const bool fuse = Z && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && g.W % 8 == 0;
-    *err = launch_repack((const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total,
-                         p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
-    *pooled = fuse;
-    if (*err != hipSuccess) return true;
-    p.in = in; p.wt = wt; p.bias = (const bf16_t *)b; p.out = (bf16_t *)Y;
-    *err = run_gather(p, variant, st);
-    return true;
+    return shape_gather(p, variant);
 }
 
-// Data gradient: dX = W^T * dY.  False when the geometry is not covered.
-bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,
-                    hipError_t *err)
+// Data gradient: one gather GEMM (input channels x input pixels) per parity class of the input
+// pixel, each with the taps that reach that class.  Every class is planned before anything is
+// launched.  *empty_class: some class has no tap at all (stride > filter) and stays zero.
+bool plan_dx(const Geom &g, int dtype, GatherParams &base, GatherParams (&cls)[4], int (&variant)[4], int *ncls, bool *empty_class)
 {
     if (!supported(g, dtype)) return false;
-    GatherParams base{};
+    base = GatherParams{};
     base.N = g.N; base.M = g.C; base.Mp = round_up(g.C, 64); base.KCp = round_up(g.K, 16);
     base.Hin = g.P; base.Win = g.Q; base.Hout = g.H; base.Wout = g.W;
     base.os = g.sh; base.is = 1; base.ntaps_total = g.R * g.S;
-    // plan every output parity class first so that nothing is launched if one does not fit
-    GatherParams cls[4];
-    int variant[4], ncls = 0;
-    bool empty_class = false;
+    *ncls = 0;
+    *empty_class = false;
     for (int a0 = 0; a0 < g.sh; ++a0)
         for (int b0 = 0; b0 < g.sw; ++b0) {
             GatherParams p = base;
@@ -648,12 +742,112 @@ bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, voi
                     p.dh[p.ntaps] = th / g.sh; p.dw[p.ntaps] = tw / g.sw; p.wtap[p.ntaps] = r * g.S + s;
                     ++p.ntaps;
                 }
-            if (p.ntaps == 0) { empty_class = true; continue; }
-            if (!shape_gather(p, &variant[ncls])) return false;
-            cls[ncls++] = p;
+            if (p.ntaps == 0) { *empty_class = true; continue; }
+            if (!shape_gather(p, &variant[*ncls])) return false;
+            cls[(*ncls)++] = p;
         }
-    const size_t in_bytes = ((size_t)g.N * g.P * g.Q * base.KCp * 2 + 255) / 256 * 256;
-    bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + in_bytes);
+    return true;
+}
+
+int describe_one(const GatherParams &p, int variant, char *buf, size_t len)
+{
+    static const int shape[6][3] = {{2, 1, 4}, {2, 2, 2}, {2, 4, 1}, {1, 1, 4}, {1, 2, 2}, {1, 4, 1}}; // NI, WM, WN
+    const int *v = shape[variant];
+    const int runs = (p.ngrp + p.gpw - 1) / p.gpw, mt = (p.Mp / 64 + v[1] - 1) / v[1];
+    return snprintf(buf, len, "gather tile=%dch x %dpx (NI=%d WM=%d WN=%d) taps=%d img/tile=%d patch=%dx%d units/wg=%d grid=%dx%dx%d lds=%dB",
+                    64 * v[1], 32 * v[0] * v[2], v[0], v[1], v[2], p.ntaps, p.IPT, p.PH, p.PWd, p.gpw, p.tiles_per_img * runs, mt,
+                    p.ksplit, 2 * p.patch_px * KCS * 2);
+}
+
+// Workspace: [channels-last input][repacked filter][float sums of shared-out channels], each
+// part starting at a multiple of 256 bytes.
+struct WsLayout { size_t in, wt, part; };
+WsLayout ws_layout(size_t in_elems, size_t wt_elems, const GatherParams &p)
+{
+    auto up = [](size_t n) { return (n + 255) / 256 * 256; };
+    WsLayout l;
+    l.in = up(in_elems * 2);
+    l.wt = up(wt_elems * 2);
+    l.part = p.ksplit > 1 ? (size_t)p.ksplit * p.N * p.M * p.Hc * p.Wc * sizeof(float) : 0;
+    return l;
+}
+
+} // namespace
+
+bool describe_conv_mfma(const Geom &g, int dtype, bool data_grad, char *buf, size_t len)
+{
+    GatherParams p{}, cls[4];
+    int variant[4], ncls = 0;
+    bool empty = false;
+    if (!data_grad) {
+        if (!plan_fwd(g, dtype, p, &variant[0])) return false;
+        describe_one(p, variant[0], buf, len);
+        return true;
+    }
+    if (!plan_dx(g, dtype, p, cls, variant, &ncls, &empty)) return false;
+    size_t at = 0;
+    for (int k = 0; k < ncls && at + 1 < len; ++k) {
+        int n = snprintf(buf + at, len - at, "%sclass(%d,%d): ", k ? "; " : "", cls[k].a0, cls[k].b0);
+        at += (size_t)max(n, 0);
+        if (at + 1 >= len) break;
+        n = describe_one(cls[k], variant[k], buf + at, len - at);
+        at += (size_t)max(n, 0);
+    }
+    return true;
+}
+
+size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad)
+{
+    GatherParams p{}, cls[4];
+    int variant[4], ncls = 0;
+    bool empty = false;
+    const size_t RS = (size_t)g.R * g.S;
+    if (!data_grad) {
+        if (!plan_fwd(g, dtype, p, &variant[0])) return 0;
+        const WsLayout l = ws_layout((size_t)g.N * g.H * g.W * p.KCp, RS * p.Mp * p.KCp, p);
+        return l.in + l.wt + l.part;
+    }
+    if (!plan_dx(g, dtype, p, cls, variant, &ncls, &empty)) return 0;
+    // (only a stride-1 data gradient, a single class, ever shares out its channels)
+    const WsLayout l = ws_layout((size_t)g.N * g.P * g.Q * p.KCp, RS * p.Mp * p.KCp, ncls == 1 ? cls[0] : p);
+    return l.in + l.wt + l.part;
+}
+
+// Forward: Y = X * W + b.  False when the geometry is not covered.
+// *pooled: Z has been written on the way (the channels-last repack reads X anyway); otherwise
+// the caller runs the compress kernel.
+bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *Z, void *ws,
+                     hipStream_t st, hipError_t *err, bool *pooled)
+{
+    *pooled = false;
+    GatherParams p{};
+    int variant;
+    if (!plan_fwd(g, dtype, p, &variant)) return false;
+    const WsLayout l = ws_layout((size_t)g.N * g.H * g.W * p.KCp, (size_t)g.R * g.S * p.Mp * p.KCp, p);
+    bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + l.in);
+    p.part = l.part ? (float *)((char *)ws + l.in + l.wt) : nullptr;
+    // whole 2 x 2 tiles, rows a multiple of 8 pixels: the pooled map falls out of the repack
+    const bool fuse = Z && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && g.W % 8 == 0;
+    *err = launch_repack((const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total,
+                         p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
+    *pooled = fuse;
+    if (*err != hipSuccess) return true;
+    p.in = in; p.wt = wt; p.bias = (const bf16_t *)b; p.out = (bf16_t *)Y;
+    *err = run_gather(p, variant, st);
+    return true;
+}
+
+// Data gradient: dX = W^T * dY.  False when the geometry is not covered.
+bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,
+                    hipError_t *err)
+{
+    GatherParams base{}, cls[4];
+    int variant[4], ncls = 0;
+    bool empty_class = false;
+    if (!plan_dx(g, dtype, base, cls, variant, &ncls, &empty_class)) return false;
+    const WsLayout l = ws_layout((size_t)g.N * g.P * g.Q * base.KCp, (size_t)g.R * g.S * base.Mp * base.KCp, ncls == 1 ? cls[0] : base);
+    bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + l.in);
+    for (int k = 0; k < ncls; ++k) cls[k].part = cls[k].ksplit > 1 ? (float *)((char *)ws + l.in + l.wt) : nullptr;
     // pixels no output pixel's tap reaches (possible when stride > filter) stay zero
     if (empty_class) {
         // (a fill kernel, not a memset node: callers may capture this call in a HIP graph)

@@ -169,3 +169,16 @@ def test_every_bf16_layer_of_the_configs_has_an_mfma_weight_gradient_plan():
             assert B.cac_workspace_size(d, B.OP_BWD_WEIGHT_COMPRESSED) == partial
             assert (partial == 0) == (slices == 1)
             assert slices * tiles <= 2048
+
+
+def test_deep_layers_on_tiny_maps_share_out_their_channel_blocks():
+    """The parity cases meant to cover the channel-split forward / data-gradient path really take it."""
+    import re
+    for N, C, K, H in ((4, 256, 128, 4), (6, 160, 96, 6)):
+        d = B.make_desc(N, C, K, H, H, 3, 3, 1, 1, 1, 1, 2, 2, dtype=B.BF16)
+        for op in (B.OP_FWD_AND_COMPRESS, B.OP_BWD_DATA):
+            plan = B.cac_describe_plan(d, op)
+            m = re.search(r"grid=(\d+)x(\d+)x(\d+)", plan)
+            assert m and int(m.group(3)) > 1, plan
+            # the float sums live in the workspace
+            assert B.cac_workspace_size(d, op) >= int(m.group(3)) * N * (K if op == B.OP_FWD_AND_COMPRESS else C) * H * H * 4

@@ -89,6 +89,10 @@ SMALL = [
     ("s2 parity classes", 3, 32, 48, 16, 16, 3, 3, 2, 1, 2),
     ("1x1 wide", 2, 128, 64, 14, 14, 1, 1, 1, 0, 2),
     ("1x1 s2 wide", 2, 96, 160, 14, 14, 1, 1, 2, 0, 4),
+    # deep layers on tiny maps: forward and data gradient share a tile's channel blocks out over
+    # several workgroups (float partial sums + a finishing pass); 160 channels = 5 blocks
+    ("4x4 maps deep", 4, 256, 128, 4, 4, 3, 3, 1, 1, 2),
+    ("6x6 maps c160", 6, 160, 96, 6, 6, 3, 3, 1, 1, 2),
 ]
 
 
