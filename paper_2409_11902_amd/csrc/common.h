@@ -31,6 +31,17 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     return (bf16_t)(u >> 16);
 }
 
+// Two floats to a pair of bfloat16 (lo in bits 15:0) with the hardware conversion
+// (v_cvt_pk_bf16_f32: round to nearest even).
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    union { bf16x2_t v; uint32_t u; } r;
+    r.v = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+    return r.u;
+}
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float *p) { return *p; }

@@ -21,6 +21,7 @@ struct GatherParams {
     int IPT, patch_px;  // images per pixel tile; patch pixels of the whole tile
     int tiles_per_img, ngrp, gpw, nkb; // tiles per image; image groups; groups per workgroup; channel blocks
     int ksplit, kbs;    // workgroups sharing one tile's channel blocks (grid z); channel blocks of each
+    int wide_store;     // the epilogue writes 16-byte runs of 8 pixels (whole planes, a multiple of 8 pixels each)
     uint32_t m_wc, m_ppi, m_pwd, m_kbs, m_img; // division magics of Wc, Hc*Wc, PWd, kbs, PH*PWd
 };
 

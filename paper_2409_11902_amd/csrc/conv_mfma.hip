@@ -58,21 +58,63 @@ struct RepackParams {
 
 __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
 {
-    __shared__ bf16_t tile[64][66];
+    constexpr int kFilterElems = 32 * (16 * 9 + 2); // a 32 x 16 block of (o, c) pairs, 9 taps, padded rows
+    __shared__ bf16_t sm[kFilterElems > 64 * 66 ? kFilterElems : 64 * 66];
     if ((int)blockIdx.x >= p.in_blocks) {
-        const long total = (long)p.RS * p.Mp * p.KCp;
-        const long idx = (long)(blockIdx.x - p.in_blocks) * 256 + threadIdx.x;
-        if (idx >= total) return;
-        const int e = idx & 7, lane = (idx >> 3) & 63;
-        long rest = idx >> 9;
-        const int mblk = rest % (p.Mp / 32);
-        rest /= p.Mp / 32;
-        const int kblk = rest % (p.KCp / 16), tap = rest / (p.KCp / 16);
-        const int m = mblk * 32 + (lane & 31), kc = kblk * 16 + 8 * (lane >> 5) + e;
-        const int o = p.transpose ? kc : m, c = p.transpose ? m : kc;
-        p.Wt[idx] = (o < p.O && c < p.Cw) ? p.W[((long)o * p.Cw + c) * p.RS + tap] : (bf16_t)0;
+        // One block per (32-row block, 16-channel block): its part of W -- for every o a contiguous
+        // run of (c, tap) -- goes through LDS as it lies in memory; then every thread gathers the
+        // 8 channels of one lane of one tap's fragment and writes them as 16 bytes, a wave one
+        // contiguous KiB.  Rows are padded to an odd number of dwords against bank conflicts.
+        const int b = blockIdx.x - p.in_blocks;
+        const int mblks = p.Mp / 32, kblks = p.KCp / 16, mblk = b % mblks, kblk = b / mblks;
+        const int rows = p.transpose ? 16 : 32, cols = p.transpose ? 32 : 16; // o rows, c columns
+        const int o0 = p.transpose ? kblk * 16 : mblk * 32, c0 = p.transpose ? mblk * 32 : kblk * 16;
+        const int L = cols * p.RS, Lp = L + 2;
+        const int wv = threadIdx.x >> 6, ln = threadIdx.x & 63;
+        // a wave takes every fourth row; all of a thread's loads are issued before the first is
+        // used (at most 8 rows of 3 x 64 elements, or 4 rows of 5 x 64)
+        constexpr int kRowsPerWave = 8, kMaxX = 5;
+        const rsrc_t rs = make_rsrc(p.W, (uint32_t)p.O * p.Cw * p.RS * 2u);
+        uint16_t tmp[kRowsPerWave][kMaxX];
+#pragma unroll
+        for (int j = 0; j < kRowsPerWave; ++j) {
+            const int r = wv + 4 * j, o = o0 + r;
+            const int lim = (r < rows && o < p.O) ? min(L, (p.Cw - c0) * p.RS) : 0; // elements of the run inside the tensor
+            const uint32_t base = ((uint32_t)(o * p.Cw + c0) * p.RS) * 2u;
+#pragma unroll
+            for (int k = 0; k < kMaxX; ++k) {
+                const int x = ln + 64 * k;
+                tmp[j][k] = __builtin_amdgcn_raw_buffer_load_b16(rs, x < lim ? base + 2u * x : kNoLoad, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kRowsPerWave; ++j) {
+            const int r = wv + 4 * j;
+#pragma unroll
+            for (int k = 0; k < kMaxX; ++k) {
+                const int x = ln + 64 * k;
+                if (r < rows && x < L) sm[r * Lp + x] = tmp[j][k];
+            }
+        }
+        __syncthreads();
+        for (int it = threadIdx.x; it < p.RS * 64; it += 256) {
+            const int tap = it >> 6, lane = it & 63, m = lane & 31, k8 = 8 * (lane >> 5);
+            u32x4 v;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t h[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int kc = k8 + 2 * k + e;
+                    h[e] = p.transpose ? sm[kc * Lp + m * p.RS + tap] : sm[m * Lp + kc * p.RS + tap];
+                }
+                v[k] = h[0] | (h[1] << 16);
+            }
+            ((u32x4 *)p.Wt)[((long)(tap * kblks + kblk) * mblks + mblk) * 64 + lane] = v;
+        }
         return;
     }
+    bf16_t (*tile)[66] = (bf16_t (*)[66])sm;
     if (p.fast) {
         // item -> (image n, block of up to 8 channel groups, pixel group pg of 8, channel group
         // within the block), the last fastest: 8 neighbouring lanes read 8 channel rows and
@@ -181,8 +223,7 @@ hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, in
     const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z ? HW / 16 : HW / 8) : 0;
     p.in_blocks = p.fast ? (int)((items + 255) / 256) : N * ((Cp + 63) / 64) * ((HW + 63) / 64);
     p.W = W; p.Wt = Wt; p.O = O; p.Cw = Cw; p.RS = RS; p.Mp = Mp; p.KCp = KCp; p.transpose = transpose;
-    const long wtotal = (long)RS * Mp * KCp;
-    hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(p.in_blocks + (wtotal + 255) / 256)), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(p.in_blocks + (Mp / 32) * (KCp / 16))), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
@@ -474,7 +515,52 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
             if (kb == p.kbs - 1) {
                 // ---- epilogue of the unit: bias, bfloat16, NCHW
                 const int n_base = (g_begin + unit) * p.IPT;
-                if constexpr (TR) {
+                if (TR && p.wide_store) {
+                    // Through LDS (a region of the wave's own, past the staging buffers), so that
+                    // the lanes of a store cover whole rows: the wave's 64 channels x NI*32 pixels
+                    // as [channel][pixel] bfloat16, rows padded by 16 bytes; then 8 pixels (16 bytes)
+                    // per lane, NI*4 neighbouring lanes one channel's run.
+                    constexpr int ROWB = NI * 64 + 16, LPR = NI * 4;
+                    unsigned char *ep = smem + 2 * buf_bytes + wave * (64 * ROWB);
+                    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) {
+                        const int m = m0 + mi * 32 + l32;
+                        const float bias = (p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                            for (int jq = 0; jq < 4; ++jq) {
+                                const f32x16 &a = acc[mi][ni];
+                                *(u32x2 *)(ep + (mi * 32 + l32) * ROWB + (ni * 32 + 8 * jq + 4 * half) * 2) =
+                                    u32x2{f32x2_to_bf16x2(a[4 * jq] + bias, a[4 * jq + 1] + bias), f32x2_to_bf16x2(a[4 * jq + 2] + bias, a[4 * jq + 3] + bias)};
+                            }
+                    }
+                    // (the wave reads what it wrote itself: LDS serves a wave's requests in order)
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    const int seg = lane % LPR, idx = wn * NI * 32 + seg * 8; // pixel of the tile
+                    int g = 0, px = pix0 + idx;
+                    if (p.IPT > 1) {
+                        g = fdiv(idx, p.m_ppi);
+                        px = idx - g * ppi;
+                    }
+                    const int n = n_base + g;
+                    const bool px_ok = px < ppi && g < p.IPT && n < p.N;
+#pragma unroll
+                    for (int it = 0; it < LPR; ++it) {
+                        const int row = it * (64 / LPR) + lane / LPR, m = m0 + row;
+                        const u32x4 v = *(const u32x4 *)(ep + row * ROWB + seg * 16);
+                        if (px_ok && m < p.M) *(u32x4 *)(p.out + ((long)n * p.M + m) * ppi + px) = v;
+                    }
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                            for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.f;
+                } else if constexpr (TR) {
                     // register j of lane l: pixel 8*(j/4) + 4*(l/32) + j%4 of the block, channel l%32
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi) {
@@ -502,8 +588,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                                         continue;
                                     }
                                     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-                                    const u32x2 v = {(uint32_t)f32_to_bf16(a[4 * jq] + bias) | ((uint32_t)f32_to_bf16(a[4 * jq + 1] + bias) << 16),
-                                                     (uint32_t)f32_to_bf16(a[4 * jq + 2] + bias) | ((uint32_t)f32_to_bf16(a[4 * jq + 3] + bias) << 16)};
+                                    const u32x2 v = {f32x2_to_bf16x2(a[4 * jq] + bias, a[4 * jq + 1] + bias), f32x2_to_bf16x2(a[4 * jq + 2] + bias, a[4 * jq + 3] + bias)};
                                     *(u32x2 *)(p.out + ((long)n * p.M + m) * ppi + px) = v;
                                 }
                             }
@@ -555,8 +640,7 @@ __global__ void __launch_bounds__(256) gather_finish_kernel(const float *__restr
     f32x4 sum = src[0];
     for (int k = 1; k < nsplit; ++k) sum += src[k * quads];
     if (bias) sum += bf16_to_f32(bias[(int)((q * 4 / ppi) % M)]);
-    const u32x2 v = {(uint32_t)f32_to_bf16(sum[0]) | ((uint32_t)f32_to_bf16(sum[1]) << 16),
-                     (uint32_t)f32_to_bf16(sum[2]) | ((uint32_t)f32_to_bf16(sum[3]) << 16)};
+    const u32x2 v = {f32x2_to_bf16x2(sum[0], sum[1]), f32x2_to_bf16x2(sum[2], sum[3])};
     *((u32x2 *)out + q) = v;
 }
 
@@ -571,7 +655,8 @@ template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_s
     }
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw;
     dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM, p.ksplit);
-    hipLaunchKernelGGL(kern, grid, dim3(512), (size_t)2 * p.patch_px * KCS * 2, st, p);
+    const size_t lds = (size_t)2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * (NI * 64 + 16) : 0);
+    hipLaunchKernelGGL(kern, grid, dim3(512), lds, st, p);
     if (p.ksplit > 1) {
         const long quads = (long)p.N * p.M * p.Hc * p.Wc / 4;
         hipLaunchKernelGGL(gather_finish_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, (const float *)p.part,
@@ -641,7 +726,7 @@ bool shape_gather(GatherParams &p, int *variant)
             }
             q.patch_px = q.IPT * q.PH * q.PWd;
             if (q.patch_px * (KC / 8) > 256 * kMaxItems) continue;
-            if ((long)2 * q.patch_px * KCS * 2 > 150 * 1024) continue;
+            if ((long)2 * q.patch_px * KCS * 2 > 110 * 1024) continue; // (leaves room for the epilogue's transpose)
             q.m_img = magic(q.PH * q.PWd);
             q.ngrp = (q.N + q.IPT - 1) / q.IPT;
             const int mtiles = (q.Mp / 64 + wm - 1) / wm;
@@ -650,6 +735,7 @@ bool shape_gather(GatherParams &p, int *variant)
                 if (q.nkb % ks) continue;
                 if (force && (wm != f_wm || ni != f_ni || ks != f_ks)) continue;
                 q.ksplit = ks;
+                q.wide_store = whole_planes && ks == 1 && ppi % 8 == 0; // 16-byte runs of pixels, aligned
                 q.kbs = q.nkb / ks;
                 q.m_kbs = magic(q.kbs);
                 // a few units per workgroup (a longer pipeline) as long as every CU still gets a workgroup
@@ -695,6 +781,7 @@ bool supported(const Geom &g, int dtype)
     // 32-bit byte offsets with 2^31 reserved for "no load"
     const long lim = 1L << 30;
     if ((long)g.N * g.H * g.W * round_up(g.C, 16) >= lim || (long)g.N * g.P * g.Q * round_up(g.K, 16) >= lim) return false;
+    if ((long)g.R * g.S * round_up(g.K, 64) * round_up(g.C, 64) >= lim) return false;
     return true;
 }
 
@@ -756,7 +843,7 @@ int describe_one(const GatherParams &p, int variant, char *buf, size_t len)
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw, mt = (p.Mp / 64 + v[1] - 1) / v[1];
     return snprintf(buf, len, "gather tile=%dch x %dpx (NI=%d WM=%d WN=%d) taps=%d img/tile=%d patch=%dx%d units/wg=%d grid=%dx%dx%d lds=%dB",
                     64 * v[1], 32 * v[0] * v[2], v[0], v[1], v[2], p.ntaps, p.IPT, p.PH, p.PWd, p.gpw, p.tiles_per_img * runs, mt,
-                    p.ksplit, 2 * p.patch_px * KCS * 2);
+                    p.ksplit, 2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * (v[0] * 64 + 16) : 0));
 }
 
 // Workspace: [channels-last input][repacked filter][float sums of shared-out channels], each
