@@ -121,7 +121,8 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
         // write the 128 contiguous bytes of 64 channels of one pixel; the next lanes move along
         // the pixels, so every row is read in 128-byte runs too.  With Z, an item is the same 8
         // pixels of TWO image rows (2h, 2h+1), from which it also forms the 2 x 2 means.
-        const bool pool = p.Z != nullptr;
+        const bool pool = p.Z != nullptr && p.Wimg != 4;
+        const bool pool4 = p.Z != nullptr && p.Wimg == 4; // rows of 4 pixels: an item is already two whole rows
         const int wgs = pool ? p.Wimg / 8 : 1;                 // pixel groups per image row
         const int pgs = pool ? p.HW / 16 : p.HW / 8;           // items along the pixels
         const int cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
@@ -162,6 +163,27 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
                     v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                 }
                 *(u32x4 *)(dst + (long)px * p.Cp) = v;
+            }
+        }
+        if (pool4) {
+            // Z[n][c][pi][0..1] from pixels (0, 1, 4, 5) and (2, 3, 6, 7) of the item, summed row by
+            // row like the stand-alone kernel does
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = cg * 8 + i;
+                if (c >= p.C) break;
+                uint32_t h2[2];
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const uint32_t t0 = r[0][i][jj], t1r = r[0][i][2 + jj];
+                    float sum = 0.f;
+                    sum += __uint_as_float(t0 << 16);
+                    sum += __uint_as_float(t0 & 0xffff0000u);
+                    sum += __uint_as_float(t1r << 16);
+                    sum += __uint_as_float(t1r & 0xffff0000u);
+                    h2[jj] = f32_to_bf16(sum * 0.25f);
+                }
+                *(uint32_t *)(p.Z + (((long)n * p.C + c) * (p.HW / 8) + pi) * 2) = h2[0] | (h2[1] << 16);
             }
         }
         if (pool) {
@@ -211,7 +233,7 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
 }
 
 // Launches the input and filter repacks of one call.
-// Z, Wimg: see RepackParams (Z null: no pooling; else HW must be a multiple of 2*Wimg and Wimg of 8).
+// Z, Wimg: see RepackParams (Z null: no pooling; else HW must be a multiple of 2*Wimg and Wimg 4 or a multiple of 8).
 hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, int Cp, const bf16_t *W, bf16_t *Wt, int O,
                          int Cw, int RS, int Mp, int KCp, int transpose, bf16_t *Z, int Wimg, hipStream_t st)
 {
@@ -220,7 +242,7 @@ hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, in
     p.Z = Z; p.Wimg = Wimg;
     p.fast = HW % 8 == 0;
     const int cgs = Cp / 8, cgw = cgs < 8 ? cgs : 8;
-    const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z ? HW / 16 : HW / 8) : 0;
+    const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z && Wimg != 4 ? HW / 16 : HW / 8) : 0;
     p.in_blocks = p.fast ? (int)((items + 255) / 256) : N * ((Cp + 63) / 64) * ((HW + 63) / 64);
     p.W = W; p.Wt = Wt; p.O = O; p.Cw = Cw; p.RS = RS; p.Mp = Mp; p.KCp = KCp; p.transpose = transpose;
     hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(p.in_blocks + (Mp / 32) * (KCp / 16))), dim3(256), 0, st, p);
@@ -415,6 +437,15 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         }
     }
 
+    // TR epilogues: a lane's output channels are fixed, so their bias is fetched here, once, and
+    // not in the epilogue, where the load's latency would lie bare
+    float bias_tr[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int m = m0 + mi * 32 + l32;
+        bias_tr[mi] = (TR && p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
+    }
+
     __syncthreads(); // buffer 0 holds stage 0
     int kb = 0, unit = 0;
     for (int s = 0; s < nstages; ++s) {
@@ -526,7 +557,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi) {
                         const int m = m0 + mi * 32 + l32;
-                        const float bias = (p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
+                        const float bias = bias_tr[mi];
 #pragma unroll
                         for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -565,7 +596,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi) {
                         const int m = m0 + mi * 32 + l32;
-                        const float bias = (p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
+                        const float bias = bias_tr[mi];
 #pragma unroll
                         for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -914,7 +945,7 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + l.in);
     p.part = l.part ? (float *)((char *)ws + l.in + l.wt) : nullptr;
     // whole 2 x 2 tiles, rows a multiple of 8 pixels: the pooled map falls out of the repack
-    const bool fuse = Z && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && g.W % 8 == 0;
+    const bool fuse = Z && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && (g.W % 8 == 0 || g.W == 4);
     *err = launch_repack((const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total,
                          p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
     *pooled = fuse;

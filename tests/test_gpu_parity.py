@@ -228,9 +228,9 @@ def test_weight_gradient_is_reproducible_bit_for_bit():
         assert np.array_equal(first, run_step(spec, t)["dW"])
 
 
-@pytest.mark.parametrize("shape", [(3, 24, 40, 16, 16), (2, 64, 64, 8, 32), (5, 70, 16, 4, 8)])
+@pytest.mark.parametrize("shape", [(3, 24, 40, 16, 16), (2, 64, 64, 8, 32), (5, 70, 16, 4, 8), (7, 72, 16, 4, 4), (3, 20, 8, 6, 4)])
 def test_pooling_fused_into_the_forward_pass_equals_the_standalone_kernel(shape):
-    """Where the forward pass forms Z on its way (2 x 2 tiles, rows a multiple of 8 pixels),
+    """Where the forward pass forms Z on its way (2 x 2 tiles, rows of 4 or a multiple of 8 pixels),
     the bits are those of cac_compress."""
     import torch
     from gpu_util import upload, workspace
