@@ -49,6 +49,8 @@ struct RepackParams {
     const bf16_t *in;
     bf16_t *out;
     int N, C, HW, Cp, in_blocks, fast;
+    int in_wpb;         // waves of an input block that take items (fast path): fewer than 4 spread a small
+                        // input over more compute units, one block each
     bf16_t *Z;          // pooled copy of `in` written on the way (2 x 2 means), or null
     int Wimg;           // image width (only with Z)
     const bf16_t *W;
@@ -126,7 +128,8 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
         const int wgs = pool ? p.Wimg / 8 : 1;                 // pixel groups per image row
         const int pgs = pool ? p.HW / 16 : p.HW / 8;           // items along the pixels
         const int cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
-        const long item = (long)blockIdx.x * 256 + threadIdx.x;
+        if ((int)(threadIdx.x >> 6) >= p.in_wpb) return;
+        const long item = ((long)blockIdx.x * p.in_wpb + (threadIdx.x >> 6)) * 64 + (threadIdx.x & 63);
         if (item >= (long)p.N * cgb * pgs * cgw) return;
         const int cl = item % cgw;
         long t1 = item / cgw;
@@ -243,7 +246,10 @@ hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, in
     p.fast = HW % 8 == 0;
     const int cgs = Cp / 8, cgw = cgs < 8 ? cgs : 8;
     const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z && Wimg != 4 ? HW / 16 : HW / 8) : 0;
-    p.in_blocks = p.fast ? (int)((items + 255) / 256) : N * ((Cp + 63) / 64) * ((HW + 63) / 64);
+    // (a thread's loads are all in flight at once, so a small input is bound by latency, not by
+    // the number of waves per compute unit: give every unit a wave before any gets a second)
+    p.in_wpb = items > 64 * 256 ? 4 : 1; // (measured: two waves per block are slower than either)
+    p.in_blocks = p.fast ? (int)((items + 64 * p.in_wpb - 1) / (64 * p.in_wpb)) : N * ((Cp + 63) / 64) * ((HW + 63) / 64);
     p.W = W; p.Wt = Wt; p.O = O; p.Cw = Cw; p.RS = RS; p.Mp = Mp; p.KCp = KCp; p.transpose = transpose;
     hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(p.in_blocks + (Mp / 32) * (KCp / 16))), dim3(256), 0, st, p);
     return hipGetLastError();
