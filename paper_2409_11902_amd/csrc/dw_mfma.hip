@@ -632,7 +632,7 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
 
     // ---- epilogue --------------------------------------------------------------------
     // accumulator register j of lane l holds row 8*(j/4) + 4*(l/32) + j%4, column l%32.
-    // The accumulators are handled as G groups of 4 registers: g = ((mi*NI + ni)*T + tap)*4 + j/4.
+    // The accumulators are handled as G groups of 4 registers: g = (j/4)*(G/4) + (mi*NI + ni)*T + tap.
     typedef __attribute__((ext_vector_type(4))) float f32x4;
     typedef f32x4 __attribute__((aligned(4))) f32x4_u;
     constexpr int G = MI * NI * T * 4;
@@ -642,6 +642,7 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
     // are dead: the loop above ends with a barrier), then adds what the other waves hand it, in
     // wave order.  red[wm, wn][source wave][g][lane].
     f32x4 *red = (f32x4 *)smem + ((wn * WM + wm) * KS) * (G * 64) + lane;
+#define CAC_G(mi, ni, t, jq) ((jq) * (G / 4) + ((mi) * NI + (ni)) * T + (t))
 #define CAC_GROUP(mi, ni, t, jq) \
     f32x4 { acc[mi][ni][t][4 * (jq)], acc[mi][ni][t][4 * (jq) + 1], acc[mi][ni][t][4 * (jq) + 2], acc[mi][ni][t][4 * (jq) + 3] }
     if constexpr (KS > 1) {
@@ -653,13 +654,23 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                 for (int t = 0; t < T; ++t)
 #pragma unroll
                     for (int jq = 0; jq < 4; ++jq)
-                        if (jq * KS / 4 != ks) red[(ks * G + ((mi * NI + ni) * T + t) * 4 + jq) * 64] = CAC_GROUP(mi, ni, t, jq);
+                        if (jq * KS / 4 != ks) red[(ks * G + CAC_G(mi, ni, t, jq)) * 64] = CAC_GROUP(mi, ni, t, jq);
         __syncthreads();
     }
     // Output: dW itself (one slice), or this slice's partial sums in the workspace, in the same
     // [o][c][tap] order, so that the sum over the slices is a plain stream.
     float *out = p.direct ? p.out : p.out + (long)slice * p.K * p.C * T;
     const bool inside = o0 + TILE_O <= p.K && c0 + TILE_C <= p.C; // no edge of dW crosses the tile
+    // Nine taps, a tile inside dW, rows of dW a multiple of 16 bytes: a group (8 output channels x
+    // 32 input channels x 9 taps) is 8 contiguous runs of 1152 bytes in memory.  It goes through
+    // a wave-private 9 KB of LDS, [row][c][tap], and leaves as 16-byte stores in which the lanes
+    // of a wave cover whole runs (a lane's own 36-byte runs, unaligned and 36 bytes apart, cost
+    // the store unit 1.5 us per group).  The 9 KB: with the pixels split over the waves, the part
+    // of `red` reserved for the groups the wave keeps from itself, which nobody writes or reads;
+    // otherwise the dead staging buffers.
+    const bool runs16 = T == 9 && inside && (p.C & 3) == 0;
+    float *tb = KS > 1 ? (float *)((f32x4 *)smem + (((wn * WM + wm) * KS + ks) * G + (ks * 4 / KS) * (G / 4)) * 64)
+                       : (float *)smem + wave * (8 * 32 * 9);
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -674,8 +685,27 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                     if constexpr (KS > 1) {
 #pragma unroll
                         for (int k2 = 0; k2 < KS; ++k2)
-                            if (k2 != ks) v[t] += red[(k2 * G + ((mi * NI + ni) * T + t) * 4 + jq) * 64];
+                            if (k2 != ks) v[t] += red[(k2 * G + CAC_G(mi, ni, t, jq)) * 64];
                     }
+                }
+                if (T == 9 && runs16) {
+#pragma unroll
+                    for (int t = 0; t < T; ++t)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) tb[half * 1152 + l32 * 9 + e * 288 + t] = v[t][e];
+                    // (the wave reads what it wrote itself: LDS serves a wave's requests in order)
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    const long row0 = (long)(o0 + (wm * MI + mi) * 32 + 8 * jq) * p.C + c0 + (wn * NI + ni) * 32;
+#pragma unroll
+                    for (int k = 0; k < 9; ++k) {
+                        const int q4 = k * 64 + lane, rr = q4 / 72, w4 = q4 - rr * 72; // row, 16-byte unit of its run
+                        *(f32x4 *)(out + (row0 + (long)rr * p.C) * 9 + 4 * w4) = ((const f32x4 *)tb)[q4];
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    continue;
                 }
                 // the T taps of one (o, c) are consecutive floats
                 const int c = c0 + (wn * NI + ni) * 32 + l32;
@@ -697,6 +727,7 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
                 }
             }
 #undef CAC_GROUP
+#undef CAC_G
 }
 
 // dW = sum over the slices of their partial sums, in slice order.  A block of 256 threads owns
@@ -850,6 +881,7 @@ bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
         q.lds_bytes = (q.XW + 2 * (q.LRpad * 8 + tile_o * q.dy_ostride + tile_c * q.x_cstride)) * 2;
         if (q.lds_bytes > lds_budget) return false;
         q.lds_bytes = max(q.lds_bytes, red_bytes); // the cross-wave sum reuses the staging space
+        q.lds_bytes = max(q.lds_bytes, var.WM * var.WN * 8 * 32 * 9 * 4); // so does the epilogue's transpose (9 KB per wave)
         return true;
     };
     // Candidates: part of one image (nbi = 1, pr <= P) or several whole images.
