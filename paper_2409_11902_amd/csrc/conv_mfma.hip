@@ -269,20 +269,25 @@ __global__ void __launch_bounds__(256) zero_fill_kernel(bf16_t *dst, long n)
 // Workgroup: 4 MFMA waves (WM x WN, a wave owns 64 (m) x 32*NI (pixels)) and 4 copy waves.
 // A pixel tile is PT = WN*NI*32 pixels of one image, or IPT whole images when an image has at
 // most PT/2 pixels.  The work of a workgroup is a run of "units" (the same tile position in
-// consecutive image groups), each unit nkb "stages" of KC input channels; the stages of the
-// whole run form one software pipeline: the copy waves keep two stages of global loads in
-// flight and write the patch of stage s+1 into the LDS buffer the MFMA waves are not reading
-// (one barrier per stage).  Filter fragments come straight from global memory (fragment order,
-// cache resident), fetched two steps ahead by the MFMA waves, whose only other memory traffic
-// is LDS reads, so their load counter never waits on the long-latency patch loads.
+// consecutive image groups), each unit kbs "stages" of KC input channels (all nkb channel blocks,
+// or this workgroup's share of them when several workgroups -- grid z -- share a tile: then the
+// epilogue writes float sums for gather_finish_kernel); the stages of the whole run form one
+// software pipeline: the copy waves keep two stages of global loads in flight and write the patch
+// of stage s+1 into the LDS buffer the MFMA waves are not reading (one barrier per stage).
+// Filter fragments come straight from global memory (fragment order, cache resident), fetched
+// ahead by the MFMA waves themselves -- six steps with nine taps (DEEP), else two -- whose only
+// other memory traffic is LDS reads, so their load counter never waits on the long-latency
+// patch loads.
 constexpr int kMaxItems = 12; // 16-byte patch items a copy thread moves per stage
 // floor(x / d) for small x (x * d < 2^32) with magic = ceil(2^32 / d), 0 standing for d = 1
 __device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t magic) { return magic ? __umulhi(x, magic) : x; }
 constexpr uint32_t kNoElem = 0x40000000u;
 
 // TR: the accumulators hold the transposed tile (lanes = output channels, registers = pixels):
-// a lane then owns runs of 4 consecutive pixels and writes them as one 8-byte store.  Used when
-// consecutive pixels of the launch are consecutive and 8-byte aligned in memory.
+// a lane then owns runs of 4 consecutive pixels.  Used when consecutive pixels of the launch are
+// consecutive and 8-byte aligned in memory; the runs leave as 8-byte stores, or, with
+// p.wide_store, through LDS as 16-byte stores that cover whole rows.
+// DEEP: nine taps; the operand rings described at their declaration.
 template <int NI, int WM, int WN, bool TR, bool DEEP>
 __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 {
