@@ -427,7 +427,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     // vector cache at full MFMA rate.  A stage is 18 steps, a multiple of D, so that step q of
     // every stage uses ring slot q % D and, once the steps are unrolled, every slot is a fixed
     // register.  The uniform part of a fragment's address goes into the load's scalar offset.
-    constexpr int D = 6, STEPS = 9 * (KC / 16);
+    constexpr int D = NI >= 4 ? 3 : 6, STEPS = 9 * (KC / 16); // (a step of NI = 4 is twice as long)
     static_assert(STEPS % D == 0, "ring slots must not move from stage to stage");
     u32x4 wr[DEEP ? D : 1][MI];
     uint32_t wl[9];
@@ -474,7 +474,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                 // pixel operands: a ring of DB steps in registers of their own (a copy from a
                 // "next" to a "current" set lets the compiler merge the two and issue the LDS read
                 // only after the current value's last use, a fraction of a step ahead)
-                constexpr int DB = 3;
+                constexpr int DB = NI >= 4 ? 2 : 3;
                 static_assert(STEPS % DB == 0, "ring slots must not move from stage to stage");
                 u32x4 bq[DB][NI];
                 auto pixels = [&](int q, int ni) { return *(const u32x4 *)(smem + buf + pbase[ni] + toff[q >> 1] + 32 * (q & 1)); };
@@ -562,39 +562,44 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                     // the lanes of a store cover whole rows: the wave's 64 channels x NI*32 pixels
                     // as [channel][pixel] bfloat16, rows padded by 16 bytes; then 8 pixels (16 bytes)
                     // per lane, NI*4 neighbouring lanes one channel's run.
-                    constexpr int ROWB = NI * 64 + 16, LPR = NI * 4;
+                    // Two pixel blocks (64 pixels) per pass, so that the region stays at 9 KB per wave.
+                    constexpr int NIB = NI < 2 ? NI : 2, ROWB = NIB * 64 + 16, LPR = NIB * 4;
                     unsigned char *ep = smem + 2 * buf_bytes + wave * (64 * ROWB);
                     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 #pragma unroll
-                    for (int mi = 0; mi < MI; ++mi) {
-                        const int m = m0 + mi * 32 + l32;
-                        const float bias = bias_tr[mi];
+                    for (int pass = 0; pass < NI / NIB; ++pass) {
 #pragma unroll
-                        for (int ni = 0; ni < NI; ++ni)
+                        for (int mi = 0; mi < MI; ++mi) {
+                            const float bias = bias_tr[mi];
 #pragma unroll
-                            for (int jq = 0; jq < 4; ++jq) {
-                                const f32x16 &a = acc[mi][ni];
-                                *(u32x2 *)(ep + (mi * 32 + l32) * ROWB + (ni * 32 + 8 * jq + 4 * half) * 2) =
-                                    u32x2{f32x2_to_bf16x2(a[4 * jq] + bias, a[4 * jq + 1] + bias), f32x2_to_bf16x2(a[4 * jq + 2] + bias, a[4 * jq + 3] + bias)};
-                            }
-                    }
-                    // (the wave reads what it wrote itself: LDS serves a wave's requests in order)
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    const int seg = lane % LPR, idx = wn * NI * 32 + seg * 8; // pixel of the tile
-                    int g = 0, px = pix0 + idx;
-                    if (p.IPT > 1) {
-                        g = fdiv(idx, p.m_ppi);
-                        px = idx - g * ppi;
-                    }
-                    const int n = n_base + g;
-                    const bool px_ok = px < ppi && g < p.IPT && n < p.N;
+                            for (int nb = 0; nb < NIB; ++nb)
 #pragma unroll
-                    for (int it = 0; it < LPR; ++it) {
-                        const int row = it * (64 / LPR) + lane / LPR, m = m0 + row;
-                        const u32x4 v = *(const u32x4 *)(ep + row * ROWB + seg * 16);
-                        if (px_ok && m < p.M) *(u32x4 *)(p.out + ((long)n * p.M + m) * ppi + px) = v;
+                                for (int jq = 0; jq < 4; ++jq) {
+                                    const f32x16 &a = acc[mi][pass * NIB + nb];
+                                    *(u32x2 *)(ep + (mi * 32 + l32) * ROWB + (nb * 32 + 8 * jq + 4 * half) * 2) =
+                                        u32x2{f32x2_to_bf16x2(a[4 * jq] + bias, a[4 * jq + 1] + bias), f32x2_to_bf16x2(a[4 * jq + 2] + bias, a[4 * jq + 3] + bias)};
+                                }
+                        }
+                        // (the wave reads what it wrote itself: LDS serves a wave's requests in order)
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        const int seg = lane % LPR, idx = (wn * NI + pass * NIB) * 32 + seg * 8; // pixel of the tile
+                        int g = 0, px = pix0 + idx;
+                        if (p.IPT > 1) {
+                            g = fdiv(idx, p.m_ppi);
+                            px = idx - g * ppi;
+                        }
+                        const int n = n_base + g;
+                        const bool px_ok = px < ppi && g < p.IPT && n < p.N;
+#pragma unroll
+                        for (int it = 0; it < LPR; ++it) {
+                            const int row = it * (64 / LPR) + lane / LPR, m = m0 + row;
+                            const u32x4 v = *(const u32x4 *)(ep + row * ROWB + seg * 16);
+                            if (px_ok && m < p.M) *(u32x4 *)(p.out + ((long)n * p.M + m) * ppi + px) = v;
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
                     }
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi)
@@ -697,7 +702,7 @@ template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_s
     }
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw;
     dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM, p.ksplit);
-    const size_t lds = (size_t)2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * (NI * 64 + 16) : 0);
+    const size_t lds = (size_t)2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * ((NI < 2 ? NI : 2) * 64 + 16) : 0);
     hipLaunchKernelGGL(kern, grid, dim3(512), lds, st, p);
     if (p.ksplit > 1) {
         const long quads = (long)p.N * p.M * p.Hc * p.Wc / 4;
@@ -754,7 +759,7 @@ bool shape_gather(GatherParams &p, int *variant)
     for (int wm : {4, 2, 1}) {
         if (wm * 64 > p.Mp && wm > 1) continue;
         const int wn = 4 / wm;
-        for (int ni : {2, 1}) {
+        for (int ni : {2, 1}) { // (NI = 4 fits the register file only with spills and measured slower)
             GatherParams q = p;
             const int pt = wn * ni * 32;
             q.IPT = 2 * ppi <= pt ? pt / ppi : 1;
@@ -784,10 +789,12 @@ bool shape_gather(GatherParams &p, int *variant)
                 q.gpw = (int)max(1L, min((long)((8 + q.kbs - 1) / q.kbs), wgs1 * ks / 256));
                 const long runs = (q.ngrp + q.gpw - 1) / q.gpw;
                 const long wgs = (long)q.tiles_per_img * runs * mtiles * ks;
-                const double step = max(64.0 * ni, 128.0) * 1.5;
+                // cycles per step as measured (vector-cache bound below NI = 4), two-step prefetch 1.35 x
+                const double step = (ni == 1 ? 150.0 : 235.0) * (q.ntaps == 9 ? 1.0 : 1.35);
                 const double t_wg = (double)q.gpw * q.kbs * 2 * q.ntaps * step + 8000.0;
                 const double l2_bytes = (double)wgs * q.gpw * q.kbs * KC * 2.0 * (q.ntaps * 64.0 * wm + q.patch_px);
                 double cost = max((double)((wgs + 255) / 256) * t_wg, l2_bytes / 6000.0 + 8000.0);
+                cost += l2_bytes / 6000.0 * 0.01; // between equals, the one that moves less
                 if (ks > 1) cost += 6000.0 + (double)ks * q.N * q.M * ppi * 8.0 / 2500.0;
                 if (cost < best_cost) {
                     best_cost = cost;
@@ -885,7 +892,7 @@ int describe_one(const GatherParams &p, int variant, char *buf, size_t len)
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw, mt = (p.Mp / 64 + v[1] - 1) / v[1];
     return snprintf(buf, len, "gather tile=%dch x %dpx (NI=%d WM=%d WN=%d) taps=%d img/tile=%d patch=%dx%d units/wg=%d grid=%dx%dx%d lds=%dB",
                     64 * v[1], 32 * v[0] * v[2], v[0], v[1], v[2], p.ntaps, p.IPT, p.PH, p.PWd, p.gpw, p.tiles_per_img * runs, mt,
-                    p.ksplit, 2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * (v[0] * 64 + 16) : 0));
+                    p.ksplit, 2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * ((v[0] < 2 ? v[0] : 2) * 64 + 16) : 0));
 }
 
 // Workspace: [channels-last input][repacked filter][float sums of shared-out channels], each
