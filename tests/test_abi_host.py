@@ -174,7 +174,7 @@ def test_every_bf16_layer_of_the_configs_has_an_mfma_weight_gradient_plan():
 def test_deep_layers_on_tiny_maps_share_out_their_channel_blocks():
     """The parity cases meant to cover the channel-split forward / data-gradient path really take it."""
     import re
-    for N, C, K, H in ((4, 256, 128, 4), (6, 160, 96, 6)):
+    for N, C, K, H in ((4, 256, 128, 4), (6, 160, 160, 6)):
         d = B.make_desc(N, C, K, H, H, 3, 3, 1, 1, 1, 1, 2, 2, dtype=B.BF16)
         for op in (B.OP_FWD_AND_COMPRESS, B.OP_BWD_DATA):
             plan = B.cac_describe_plan(d, op)

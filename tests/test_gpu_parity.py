@@ -92,7 +92,7 @@ SMALL = [
     # deep layers on tiny maps: forward and data gradient share a tile's channel blocks out over
     # several workgroups (float partial sums + a finishing pass); 160 channels = 5 blocks
     ("4x4 maps deep", 4, 256, 128, 4, 4, 3, 3, 1, 1, 2),
-    ("6x6 maps c160", 6, 160, 96, 6, 6, 3, 3, 1, 1, 2),
+    ("6x6 maps c160", 6, 160, 160, 6, 6, 3, 3, 1, 1, 2),
 ]
 
 
