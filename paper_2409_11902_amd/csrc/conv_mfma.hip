@@ -278,7 +278,7 @@ __global__ void __launch_bounds__(256) zero_fill_kernel(bf16_t *dst, long n)
 // ahead by the MFMA waves themselves -- six steps with nine taps (DEEP), else two -- whose only
 // other memory traffic is LDS reads, so their load counter never waits on the long-latency
 // patch loads.
-constexpr int kMaxItems = 12; // 16-byte patch items a copy thread moves per stage
+constexpr int kMaxItems = 12; // 16-byte patch items a copy thread moves per stage, at most (kernel parameter ITEMS: 6 or 12)
 // floor(x / d) for small x (x * d < 2^32) with magic = ceil(2^32 / d), 0 standing for d = 1
 __device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t magic) { return magic ? __umulhi(x, magic) : x; }
 constexpr uint32_t kNoElem = 0x40000000u;
@@ -288,7 +288,7 @@ constexpr uint32_t kNoElem = 0x40000000u;
 // consecutive and 8-byte aligned in memory; the runs leave as 8-byte stores, or, with
 // p.wide_store, through LDS as 16-byte stores that cover whole rows.
 // DEEP: nine taps; the operand rings described at their declaration.
-template <int NI, int WM, int WN, bool TR, bool DEEP>
+template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS>
 __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 {
     constexpr int MI = 2;
@@ -312,9 +312,9 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         const int tid = threadIdx.x - 256;
         const int items = p.patch_px * (KC / 8);
         const int v8 = (tid & 3) * 8;               // channel offset of this lane's items in the stage
-        uint32_t eq[kMaxItems], gq[kMaxItems], lq[kMaxItems];
+        uint32_t eq[ITEMS], gq[ITEMS], lq[ITEMS];
 #pragma unroll
-        for (int q = 0; q < kMaxItems; ++q) {
+        for (int q = 0; q < ITEMS; ++q) {
             const int it = tid + 256 * q;
             const int pp = it >> 2;
             const int g = fdiv(pp, p.m_img), rem = pp - g * (p.PH * p.PWd);
@@ -328,24 +328,24 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         const rsrc_t rs_in = make_rsrc(p.in, (uint32_t)p.N * p.Hin * p.Win * p.KCp * 2u);
         // global -> registers for stage s (dead stages load nothing but are issued all the same:
         // the number of loads in flight is then the same on every path)
-        auto fetch = [&](int s, u32x4 (&r)[kMaxItems]) {
+        auto fetch = [&](int s, u32x4 (&r)[ITEMS]) {
             const int u = fdiv(s, p.m_kbs), kb = kb0 + s - u * p.kbs;
             const int n_base = (g_begin + u) * p.IPT;
             const uint32_t sbase = (uint32_t)n_base * p.Hin * p.Win * p.KCp + kb * KC;
             const bool lane_ok = s < nstages && kb * KC + v8 < p.KCp;
             const uint32_t lim = lane_ok ? (uint32_t)max(p.N - n_base, 0) : 0u;
 #pragma unroll
-            for (int q = 0; q < kMaxItems; ++q) {
+            for (int q = 0; q < ITEMS; ++q) {
                 const uint32_t e = gq[q] < lim ? eq[q] + sbase : kNoElem;
                 r[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_in, e * 2u, 0, 0);
             }
         };
-        auto put = [&](uint32_t buf, const u32x4 (&r)[kMaxItems]) {
+        auto put = [&](uint32_t buf, const u32x4 (&r)[ITEMS]) {
 #pragma unroll
-            for (int q = 0; q < kMaxItems; ++q)
+            for (int q = 0; q < ITEMS; ++q)
                 if (lq[q] != 0xffffffffu) *(u32x4 *)(smem + buf + lq[q]) = r[q];
         };
-        u32x4 ra[kMaxItems], rb[kMaxItems];
+        u32x4 ra[ITEMS], rb[ITEMS];
         fetch(0, ra);
         fetch(1, rb);
         put(0, ra);
@@ -691,9 +691,9 @@ __global__ void __launch_bounds__(256) gather_finish_kernel(const float *__restr
     *((u32x2 *)out + q) = v;
 }
 
-template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_shape(const GatherParams &p, hipStream_t st)
+template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS> hipError_t launch_gather_items(const GatherParams &p, hipStream_t st)
 {
-    auto kern = conv_gather_kernel<NI, WM, WN, TR, DEEP>;
+    auto kern = conv_gather_kernel<NI, WM, WN, TR, DEEP, ITEMS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -710,6 +710,13 @@ template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_s
                            p.bias, p.out, quads, p.ksplit, p.Hc * p.Wc, p.M);
     }
     return hipGetLastError();
+}
+
+// (small patches: half the items, half the loads per stage and a shorter start-up)
+template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_shape(const GatherParams &p, hipStream_t st)
+{
+    return p.patch_px * (KC / 8) <= 256 * 6 ? launch_gather_items<NI, WM, WN, TR, DEEP, 6>(p, st)
+                                            : launch_gather_items<NI, WM, WN, TR, DEEP, kMaxItems>(p, st);
 }
 
 template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p, hipStream_t st)
