@@ -36,9 +36,11 @@ constexpr int KCS = KC + 8;  // LDS elements per patch pixel: 80 bytes, an odd n
 // Both repacks of a call in one launch.
 //
 // Input: in [N][C][HW] -> out [N][HW][Cp], zeros for c >= C.
-//   HW a multiple of 8: a thread moves an 8 channel x 8 pixel block: eight 16-byte loads along
-//   the pixels (consecutive lanes = consecutive pixel groups of a channel row), an 8 x 8
-//   transpose in registers (v_perm), eight 16-byte stores of 8 channels each.
+//   HW even (every plane starts at a multiple of 4 bytes): a thread moves an 8 channel x 8 pixel
+//   block: eight 16-byte loads along the pixels (consecutive lanes = consecutive pixel groups of
+//   a channel row), an 8 x 8 transpose in registers (v_perm), eight 16-byte stores of 8 channels
+//   each; the last block of a plane may be partial (it reads on into the next plane, or zeros
+//   past the tensor, and stores only its own pixels).
 //   Otherwise: 64 x 64 tiles through LDS, element by element.
 // Filter: W [O][C][R][S] -> Wt in MFMA fragment order [R*S][KCp/16][Mp/32][lane 64][8]: lane l of
 //   a wave holds row m = 32*mblk + l%32 and the 8 channels kc = 16*kblk + 8*(l/32) ..., so a wave
@@ -126,7 +128,7 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
         const bool pool = p.Z != nullptr && p.Wimg != 4;
         const bool pool4 = p.Z != nullptr && p.Wimg == 4; // rows of 4 pixels: an item is already two whole rows
         const int wgs = pool ? p.Wimg / 8 : 1;                 // pixel groups per image row
-        const int pgs = pool ? p.HW / 16 : p.HW / 8;           // items along the pixels
+        const int pgs = pool ? p.HW / 16 : (p.HW + 7) / 8;     // items along the pixels (the last may be partial)
         const int cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
         if ((int)(threadIdx.x >> 6) >= p.in_wpb) return;
         const long item = ((long)blockIdx.x * p.in_wpb + (threadIdx.x >> 6)) * 64 + (threadIdx.x & 63);
@@ -165,7 +167,7 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
                     const uint32_t lo = r[a][2 * k][px / 2], hi = r[a][2 * k + 1][px / 2];
                     v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                 }
-                *(u32x4 *)(dst + (long)px * p.Cp) = v;
+                if (px0 + px < p.HW) *(u32x4 *)(dst + (long)px * p.Cp) = v; // (a plane's last item may reach past it)
             }
         }
         if (pool4) {
@@ -243,9 +245,9 @@ hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, in
     RepackParams p{};
     p.in = in; p.out = out; p.N = N; p.C = C; p.HW = HW; p.Cp = Cp;
     p.Z = Z; p.Wimg = Wimg;
-    p.fast = HW % 8 == 0;
+    p.fast = HW % 2 == 0; // planes start at multiples of 4 bytes: 16-byte loads need no more
     const int cgs = Cp / 8, cgw = cgs < 8 ? cgs : 8;
-    const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z && Wimg != 4 ? HW / 16 : HW / 8) : 0;
+    const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z && Wimg != 4 ? HW / 16 : (HW + 7) / 8) : 0;
     // (a thread's loads are all in flight at once, so a small input is bound by latency, not by
     // the number of waves per compute unit: give every unit a wave before any gets a second)
     p.in_wpb = items > 64 * 256 ? 4 : 1; // (measured: two waves per block are slower than either)
