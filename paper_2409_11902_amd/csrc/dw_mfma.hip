@@ -962,8 +962,14 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
         }
     }
     if (!have_whole && !have_split) return false;
-    const int thr = g.R == 1 ? 12 : 48; // measured break-even (chunks per workgroup)
-    const bool use_split = have_split && (!have_whole || split.p.chunks_per_slice <= thr);
+    const int thr = g.R == 1 ? 12 : 24; // measured break-even (chunks per workgroup: split wins at 16, loses at 32)
+    bool use_split = have_split && (!have_whole || split.p.chunks_per_slice <= thr);
+#ifdef CAC_TUNING // development builds: CAC_DW_SHAPE=whole|split overrides the rule
+    if (const char *f = getenv("CAC_DW_SHAPE")) {
+        if (f[0] == 'w' && have_whole) use_split = false;
+        if (f[0] == 's' && have_split) use_split = true;
+    }
+#endif
     *plan = use_split ? split : whole;
     return true;
 }
