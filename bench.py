@@ -203,9 +203,15 @@ def main():
             e[3].record(stream)
             evs.append((i, e))
     torch.cuda.synchronize()
+    # median over the repetitions: these launches come from Python, and a repetition in which the
+    # host fell behind the GPU (the interval then contains idle time) must not shift the figure
+    samples = {n: [[] for _ in layers] for n in names}
     for i, e in evs:
         for j, n in enumerate(names):
-            acc[n][i] += e[j].elapsed_time(e[j + 1]) / nrep  # ms
+            samples[n][i].append(e[j].elapsed_time(e[j + 1]))  # ms
+    for n in names:
+        for i in range(len(layers)):
+            acc[n][i] = float(np.median(samples[n][i]))
 
     # ---- the weight-gradient call alone: back-to-back launches between two events on the launch stream
     dw_ms = time_dw(layers, B, torch, stream)
