@@ -5,7 +5,7 @@
 namespace cac {
 
 struct GatherParams {
-    const bf16_t *in;   // [N][Hin][Win][KCp], channels last
+    const bf16_t *in;   // [N][Hin][Win][KCp], channels last; with nchw: the caller's tensor itself, [N][KCin][Hin][Win]
     const bf16_t *wt;   // [ntaps_total][KCp/16][Mp/32][64][8], MFMA fragment order
     const bf16_t *bias; // [M] or null
     bf16_t *out;        // [N][M][Hout][Wout]
@@ -21,6 +21,7 @@ struct GatherParams {
     int IPT, patch_px;  // images per pixel tile; patch pixels of the whole tile
     int tiles_per_img, ngrp, gpw, nkb; // tiles per image; image groups; groups per workgroup; channel blocks
     int ksplit, kbs;    // workgroups sharing one tile's channel blocks (grid z); channel blocks of each
+    int nchw, KCin;     // the kernel reads the input in its own layout (KCin channels) instead of a channels-last copy
     int wide_store;     // the epilogue writes 16-byte runs of 8 pixels (whole planes, a multiple of 8 pixels each)
     uint32_t m_wc, m_ppi, m_pwd, m_kbs, m_img; // division magics of Wc, Hc*Wc, PWd, kbs, PH*PWd
 };

@@ -246,6 +246,7 @@ hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, in
     p.in = in; p.out = out; p.N = N; p.C = C; p.HW = HW; p.Cp = Cp;
     p.Z = Z; p.Wimg = Wimg;
     p.fast = HW % 2 == 0; // planes start at multiples of 4 bytes: 16-byte loads need no more
+    if (!in) N = 0;       // filter only
     const int cgs = Cp / 8, cgw = cgs < 8 ? cgs : 8;
     const long items = p.fast ? (long)N * ((cgs + cgw - 1) / cgw) * cgw * (Z && Wimg != 4 ? HW / 16 : (HW + 7) / 8) : 0;
     // (a thread's loads are all in flight at once, so a small input is bound by latency, not by
@@ -290,7 +291,7 @@ constexpr uint32_t kNoElem = 0x40000000u;
 // consecutive and 8-byte aligned in memory; the runs leave as 8-byte stores, or, with
 // p.wide_store, through LDS as 16-byte stores that cover whole rows.
 // DEEP: nine taps; the operand rings described at their declaration.
-template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS>
+template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS, bool NCHW>
 __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 {
     constexpr int MI = 2;
@@ -312,6 +313,85 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     if (wave_id >= 4) {
         // =========================== copy waves ===========================================
         const int tid = threadIdx.x - 256;
+        if constexpr (NCHW) {
+            // The input in its own layout [N][Cin][Hin][Win] (Win even): an item is 8 channels x 8
+            // pixels of one patch row, as in the repack kernel: eight 16-byte loads along the
+            // row (4-byte aligned at least), an 8 x 8 transpose in registers, eight 16-byte
+            // LDS writes of one pixel's 8 channels each.  Items exist for the image's own
+            // columns only; what lies outside the image is zero in both buffers from the start
+            // and is never written.  ITEMS here: items per thread (1 or 2).
+            const int GX = (p.Win + 7) >> 3;           // 8-pixel groups of an image row
+            const int nitems = p.IPT * p.PH * GX * (KC / 8);
+            uint32_t e0[ITEMS], l0[ITEMS], m8[ITEMS], gq[ITEMS];
+            const int co = tid & 3;                    // channel octet of the stage
+#pragma unroll
+            for (int q = 0; q < ITEMS; ++q) {
+                const int it = tid + 256 * q;
+                int rest = it >> 2;
+                const int gx = rest % GX;
+                rest /= GX;
+                const int pr = rest % p.PH, g = rest / p.PH;
+                const int hin = hin0 + pr, w0 = gx * 8;
+                const bool ok = it < nitems && hin >= 0 && hin < p.Hin;
+                uint32_t m = 0;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int w = w0 + k;               // written: inside the image and inside the patch
+                    if (ok && w < p.Win && w >= win0 && w < win0 + p.PWd) m |= 1u << k;
+                }
+                m8[q] = m;
+                gq[q] = g;
+                e0[q] = ok ? (uint32_t)((g * p.KCin + co * 8) * p.Hin + hin) * p.Win + w0 : kNoElem;
+                l0[q] = (uint32_t)(((g * p.PH + pr) * p.PWd + (w0 - win0)) * KCS + co * 8) * 2u; // (used under the mask only)
+            }
+            const rsrc_t rs_in = make_rsrc(p.in, (uint32_t)p.N * p.KCin * p.Hin * p.Win * 2u);
+            const uint32_t plane = (uint32_t)p.Hin * p.Win;
+            auto fetch = [&](int s, u32x4 (&r)[ITEMS][8]) {
+                const int u = fdiv(s, p.m_kbs), kb = kb0 + s - u * p.kbs;
+                const int n_base = (g_begin + u) * p.IPT;
+                const uint32_t sbase = (uint32_t)(n_base * p.KCin + kb * KC) * plane;
+                const int c_first = kb * KC + co * 8;   // the item's first channel
+                const uint32_t lim = s < nstages ? (uint32_t)max(p.N - n_base, 0) : 0u;
+#pragma unroll
+                for (int q = 0; q < ITEMS; ++q)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const uint32_t e = (gq[q] < lim && c_first + i < p.KCin) ? e0[q] + sbase + i * plane : kNoElem;
+                        r[q][i] = __builtin_amdgcn_raw_buffer_load_b128(rs_in, e * 2u, 0, 0);
+                    }
+            };
+            auto put = [&](uint32_t buf, const u32x4 (&r)[ITEMS][8]) {
+#pragma unroll
+                for (int q = 0; q < ITEMS; ++q)
+#pragma unroll
+                    for (int px = 0; px < 8; ++px) {
+                        u32x4 v; // pixel px of the 8 channels: half px%2 of dword px/2 of every row
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const uint32_t lo = r[q][2 * k][px / 2], hi = r[q][2 * k + 1][px / 2];
+                            v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                        }
+                        if (m8[q] & (1u << px)) *(u32x4 *)(smem + buf + l0[q] + px * (KCS * 2)) = v;
+                    }
+            };
+            u32x4 ra[ITEMS][8], rb[ITEMS][8];
+            fetch(0, ra);
+            fetch(1, rb);
+            for (uint32_t i = tid; i < 2 * buf_bytes / 16; i += 256) ((u32x4 *)smem)[i] = u32x4{0, 0, 0, 0};
+            __syncthreads(); // (the zeros of one thread lie where another writes pixels)
+            put(0, ra);
+            __syncthreads();
+            for (int s = 0; s < nstages; s += 2) {
+                fetch(s + 2, ra);
+                put(buf_bytes, rb);
+                __syncthreads();
+                if (s + 1 >= nstages) break;
+                fetch(s + 3, rb);
+                put(0, ra);
+                __syncthreads();
+            }
+            return;
+        }
         const int items = p.patch_px * (KC / 8);
         const int v8 = (tid & 3) * 8;               // channel offset of this lane's items in the stage
         uint32_t eq[ITEMS], gq[ITEMS], lq[ITEMS];
@@ -459,6 +539,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         bias_tr[mi] = (TR && p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
     }
 
+    if constexpr (NCHW) __syncthreads(); // the copy waves have zeroed both buffers
     __syncthreads(); // buffer 0 holds stage 0
     int kb = 0, unit = 0;
     for (int s = 0; s < nstages; ++s) {
@@ -693,9 +774,9 @@ __global__ void __launch_bounds__(256) gather_finish_kernel(const float *__restr
     *((u32x2 *)out + q) = v;
 }
 
-template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS> hipError_t launch_gather_items(const GatherParams &p, hipStream_t st)
+template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS, bool NCHW> hipError_t launch_gather_items(const GatherParams &p, hipStream_t st)
 {
-    auto kern = conv_gather_kernel<NI, WM, WN, TR, DEEP, ITEMS>;
+    auto kern = conv_gather_kernel<NI, WM, WN, TR, DEEP, ITEMS, NCHW>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -717,8 +798,11 @@ template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS> hipError_t laun
 // (small patches: half the items, half the loads per stage and a shorter start-up)
 template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_shape(const GatherParams &p, hipStream_t st)
 {
-    return p.patch_px * (KC / 8) <= 256 * 6 ? launch_gather_items<NI, WM, WN, TR, DEEP, 6>(p, st)
-                                            : launch_gather_items<NI, WM, WN, TR, DEEP, kMaxItems>(p, st);
+    if (p.nchw) // items of 8 x 8 elements, one or two per copy thread
+        return p.IPT * p.PH * ((p.Win + 7) / 8) * (KC / 8) <= 256 ? launch_gather_items<NI, WM, WN, TR, DEEP, 1, true>(p, st)
+                                                                   : launch_gather_items<NI, WM, WN, TR, DEEP, 2, true>(p, st);
+    return p.patch_px * (KC / 8) <= 256 * 6 ? launch_gather_items<NI, WM, WN, TR, DEEP, 6, false>(p, st)
+                                            : launch_gather_items<NI, WM, WN, TR, DEEP, kMaxItems, false>(p, st);
 }
 
 template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p, hipStream_t st)
@@ -894,6 +978,17 @@ bool plan_dx(const Geom &g, int dtype, GatherParams &base, GatherParams (&cls)[4
     return true;
 }
 
+// The data gradient reads dY where it lies when every class's patch splits into at most 512
+// items of 8 x 8 elements (rows of an even number of pixels): no channels-last copy, only the
+// filter repack.  It pays where the copy is the larger part of the repack launch (measured:
+// 3.8 us gained per call at 230 input elements per filter element, 1.5 us lost at 3.5).
+bool dx_reads_in_place(const Geom &g, const GatherParams (&cls)[4], int ncls)
+{
+    bool direct = g.Q % 2 == 0 && (long)g.N * g.K * g.P * g.Q >= 8L * g.R * g.S * g.K * g.C;
+    for (int k = 0; k < ncls; ++k) direct = direct && cls[k].IPT * cls[k].PH * ((g.Q + 7) / 8) * (KC / 8) <= 512;
+    return direct;
+}
+
 int describe_one(const GatherParams &p, int variant, char *buf, size_t len)
 {
     static const int shape[6][3] = {{2, 1, 4}, {2, 2, 2}, {2, 4, 1}, {1, 1, 4}, {1, 2, 2}, {1, 4, 1}}; // NI, WM, WN
@@ -938,6 +1033,7 @@ bool describe_conv_mfma(const Geom &g, int dtype, bool data_grad, char *buf, siz
         n = describe_one(cls[k], variant[k], buf + at, len - at);
         at += (size_t)max(n, 0);
     }
+    if (at + 1 < len && dx_reads_in_place(g, cls, ncls)) snprintf(buf + at, len - at, "; dY read in place");
     return true;
 }
 
@@ -999,10 +1095,14 @@ bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, voi
         const long n = (long)g.N * g.C * g.H * g.W;
         hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n / 8 + 256) / 256)), dim3(256), 0, st, (bf16_t *)dX, n);
     }
-    *err = launch_repack((const bf16_t *)dY, in, g.N, g.K, g.P * g.Q, base.KCp, (const bf16_t *)W, wt, g.K, g.C,
+    const bool direct = dx_reads_in_place(g, cls, ncls);
+    *err = launch_repack(direct ? nullptr : (const bf16_t *)dY, in, g.N, g.K, g.P * g.Q, base.KCp, (const bf16_t *)W, wt, g.K, g.C,
                          base.ntaps_total, base.Mp, base.KCp, 1, nullptr, 0, st);
     for (int k = 0; k < ncls && *err == hipSuccess; ++k) {
-        cls[k].in = in; cls[k].wt = wt; cls[k].bias = nullptr; cls[k].out = (bf16_t *)dX;
+        cls[k].in = direct ? (const bf16_t *)dY : in;
+        cls[k].nchw = direct;
+        cls[k].KCin = g.K;
+        cls[k].wt = wt; cls[k].bias = nullptr; cls[k].out = (bf16_t *)dX;
         *err = run_gather(cls[k], variant[k], st);
     }
     return true;

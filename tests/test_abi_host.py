@@ -182,3 +182,12 @@ def test_deep_layers_on_tiny_maps_share_out_their_channel_blocks():
             assert m and int(m.group(3)) > 1, plan
             # the float sums live in the workspace
             assert B.cac_workspace_size(d, op) >= int(m.group(3)) * N * (K if op == B.OP_FWD_AND_COMPRESS else C) * H * H * 4
+
+
+def test_data_gradient_reads_dy_in_place_where_pixels_outnumber_the_filter():
+    """The parity cases meant for the in-place data-gradient path take it; a filter-heavy layer does not."""
+    for N, C, K, H, st in ((16, 32, 32, 16, 1), (48, 32, 32, 16, 2), (40, 24, 20, 12, 1)):
+        d = B.make_desc(N, C, K, H, H, 3, 3, st, st, 1, 1, 2, 2, dtype=B.BF16)
+        assert "dY read in place" in B.cac_describe_plan(d, B.OP_BWD_DATA)
+    d = B.make_desc(128, 512, 512, 4, 4, 3, 3, 1, 1, 1, 1, 2, 2, dtype=B.BF16)
+    assert "dY read in place" not in B.cac_describe_plan(d, B.OP_BWD_DATA)

@@ -93,6 +93,12 @@ SMALL = [
     # several workgroups (float partial sums + a finishing pass); 160 channels = 5 blocks
     ("4x4 maps deep", 4, 256, 128, 4, 4, 3, 3, 1, 1, 2),
     ("6x6 maps c160", 6, 160, 160, 6, 6, 3, 3, 1, 1, 2),
+    # many pixels per filter element: the data gradient reads dY where it lies (8 x 8 transposes in
+    # its copy waves) instead of a channels-last copy; stride 2 (four classes), a row of 12 pixels
+    # (a partial 8-pixel group), 20 channels (a partial channel octet)
+    ("dY in place", 16, 32, 32, 16, 16, 3, 3, 1, 1, 2),
+    ("dY in place s2", 48, 32, 32, 16, 16, 3, 3, 2, 1, 2),
+    ("dY in place w12 k20", 40, 24, 20, 12, 12, 3, 3, 1, 1, 2),
 ]
 
 
