@@ -21,6 +21,7 @@ struct DwMfmaParams {
     int LDY, ldy_log2, dy_passes; // lanes sharing an output channel in the dY copy; passes per chunk
     int LPC, lpc_log2, z_passes;  // same for the Z copy
     int dy_ostride, x_cstride;    // LDS elements per output channel / per input channel
+    int dy_direct;       // dY can go from global memory straight into LDS (see the kernel)
     int lds_bytes;
     uint32_t m_segs, m_pr, m_zv, m_nz, m_rb;
     int nchunks, chunks_per_slice, nslices;

@@ -142,7 +142,7 @@ __device__ __forceinline__ u32x4 mask8(int left)
 // SC: the number of 8-pixel segments per output row when it is known at compile
 // time (0: read from the plan).  With SC the walk along a row is unrolled and the
 // segment offsets become immediates of the LDS reads.
-template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS, int SC>
+template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS, int SC, bool DYL>
 __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParams p)
 {
     constexpr int T = R * S;
@@ -258,11 +258,13 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
             const bool dy_in = live && s.n0 + (int)dy_ni < p.N && s.p0 + (int)dy_pr < p.P;
             const uint32_t e_dy = dy_in ? s.dy + dy_lane : kNoElem;
             const uint32_t e_z = live ? s.z + z_lane : kNoElem; // rows past Hp are never looked at
+            if constexpr (!DYL) {
 #pragma unroll
-            for (int i = 0; i < kMaxDy; ++i) {
-                // items past the last pass: offset 2^30 elements as well (uniform select)
-                const uint32_t e = e_dy + (i < p.dy_passes ? i * dy_istep : kNoElem);
-                rdy[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, (e & ~1u) * 2u, 0, 0);
+                for (int i = 0; i < kMaxDy; ++i) {
+                    // items past the last pass: offset 2^30 elements as well (uniform select)
+                    const uint32_t e = e_dy + (i < p.dy_passes ? i * dy_istep : kNoElem);
+                    rdy[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, (e & ~1u) * 2u, 0, 0);
+                }
             }
 #pragma unroll
             for (int i = 0; i < kMaxZ; ++i) {
@@ -271,6 +273,25 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
             }
         };
         const int cw = __builtin_amdgcn_readfirstlane(tid >> 6); // index among the copy waves
+        // DYL: dY goes from global memory straight into the LDS buffer (no registers, no LDS
+        // store instructions).  A load of this kind writes the 64 lanes' 16 bytes side by side
+        // from a uniform LDS address on, which is this kernel's dY layout when a wave's 64
+        // lanes are the 64 items of one output channel and no item needs a mask (the plan sets
+        // dy_direct then); lanes without a row, and chunks that do not exist, load zeros.
+        auto load_dy = [&](int ci, bool live, uint32_t base) {
+            const Src s = src_of(ci);
+            const bool dy_in = live && s.n0 + (int)dy_ni < p.N && s.p0 + (int)dy_pr < p.P;
+            const uint32_t e_dy = dy_in ? s.dy + dy_lane : kNoElem;
+            __attribute__((address_space(3))) unsigned char *l3 = (__attribute__((address_space(3))) unsigned char *)smem;
+#pragma unroll
+            for (int i = 0; i < kMaxDy; ++i) {
+                const uint32_t off = __builtin_amdgcn_readfirstlane((base + rows_elems + (cw + i * dy_opp) * p.dy_ostride) * 2u);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (__attribute__((address_space(3))) void *)(l3 + off), 16,
+                                                         (e_dy + i * dy_istep) * 2u, 0, 0, 0);
+            }
+        };
+        // DYL: everything but the Z loads of the youngest fetch has arrived, this chunk's dY too
+        auto dy_landed = [&]() { __builtin_amdgcn_s_waitcnt((kMaxZ & 0xF) | ((kMaxZ >> 4) << 14) | 0x0F70); };
         // ---- registers -> LDS buffer at element offset `base` (with the horizontal inflation)
         auto stage = [&](int ci, uint32_t base, const u32x4 (&rdy)[kMaxDy], const u32x4 (&rz)[kMaxZ]) {
             // Everything but the kMaxDy + kMaxZ loads of the younger chunk has arrived.  Said
@@ -301,14 +322,15 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
             // dY: fix-ups for all items first (they exchange data between lanes), then one
             // predicated run of stores
             u32x4 val[kMaxDy];
-            if (dy_odd) {
+            if constexpr (DYL) {
+            } else if (dy_odd) {
 #pragma unroll
                 for (int i = 0; i < kMaxDy; ++i) val[i] = fix8(rdy[i], s.dy + dy_rel + i * dy_istep, dy_mask, true);
             } else {
 #pragma unroll
                 for (int i = 0; i < kMaxDy; ++i) val[i] = rdy[i] & dy_mask;
             }
-            if (dy_write) {
+            if (!DYL && dy_write) {
                 bf16_t *d = sW + base + dy_lds;
 #pragma unroll
                 for (int i = 0; i < kMaxDy; ++i)
@@ -400,22 +422,28 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
 #pragma unroll
             for (int h = 0; h < 2; ++h)
                 rag[ph][h] = mask8((p.W - ph + SG - 1) / SG - (int)(z_zv << (3 + max(f_log2, 0))) - 8 * h);
+        if constexpr (DYL) load_dy(ci_begin, true, base0);
         zero_fill(); // in the shadow of the first loads
         __syncthreads();
         stage(ci_begin, base0, dyA, zA);
         fetch(ci_begin + 2, ci_begin + 2 < ci_end, dyA, zA);
+        if constexpr (DYL) dy_landed();
         __syncthreads(); // buffer 0 holds the first chunk
         for (int ci = ci_begin; ci < ci_end; ci += 2) {
             // MFMA waves are on buffer 0 (chunk ci); set B holds chunk ci+1, set A chunk ci+2.
             // (A chunk past the end is staged all the same -- zeros into a buffer nobody reads
             // any more -- so that every path consumes every load.)
+            if constexpr (DYL) load_dy(ci + 1, ci + 1 < ci_end, base1); // (buffer 1 is free since the last barrier)
             stage(ci + 1, base1, dyB, zB);
             fetch(ci + 3, ci + 3 < ci_end, dyB, zB);
+            if constexpr (DYL) dy_landed();
             __syncthreads();
             if (ci + 1 >= ci_end) break;
             // MFMA waves are on buffer 1 (chunk ci+1); set A holds chunk ci+2, set B chunk ci+3
+            if constexpr (DYL) load_dy(ci + 2, ci + 2 < ci_end, base0);
             stage(ci + 2, base0, dyA, zA);
             fetch(ci + 4, ci + 4 < ci_end, dyA, zA);
+            if constexpr (DYL) dy_landed();
             __syncthreads();
         }
         if constexpr (KS > 1) __syncthreads(); // the barrier inside the MFMA waves' cross-wave sum
@@ -772,10 +800,10 @@ struct Variant {
     hipError_t (*launch)(const DwMfmaParams &, dim3, hipStream_t);
 };
 
-template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS, int SC>
+template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS, int SC, bool DYL = false>
 hipError_t launch_fixed(const DwMfmaParams &p, dim3 grid, hipStream_t st)
 {
-    auto kern = dw_mfma_kernel<R, S, SG, PAD, MI, NI, WM, WN, KS, SC>;
+    auto kern = dw_mfma_kernel<R, S, SG, PAD, MI, NI, WM, WN, KS, SC, DYL>;
     static bool attr_set = false; // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -789,6 +817,16 @@ hipError_t launch_fixed(const DwMfmaParams &p, dim3 grid, hipStream_t st)
 template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS>
 hipError_t launch_variant(const DwMfmaParams &p, dim3 grid, hipStream_t st)
 {
+    if constexpr (S == 3 && SG == 1 && KS == 4) {
+        if (p.dy_direct) {
+            switch (p.SEGS) {
+            case 1: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 1, true>(p, grid, st);
+            case 2: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 2, true>(p, grid, st);
+            case 4: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 4, true>(p, grid, st);
+            default: break;
+            }
+        }
+    }
     if constexpr (S == 3 && SG == 1) {
         switch (p.SEGS) {
         case 1: return launch_fixed<R, S, SG, PAD, MI, NI, WM, WN, KS, 1>(p, grid, st);
@@ -878,6 +916,7 @@ bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
         // wave (one output channel / input channel each) read distinct LDS banks
         q.dy_ostride = 8 * ((q.rowitems + 1) | 1); // + one block: the dY window looks one block past a row
         q.x_cstride = 8 * (((nbi * nz + 1) * (q.XW / 8)) | 1); // + the zero slot
+        q.dy_direct = g.Q % 8 == 0 && q.rowitems == 64 && q.LDY == 64 && q.dy_passes == 8 && (q.SEGS == 1 || q.SEGS == 2 || q.SEGS == 4);
         q.lds_bytes = (q.XW + 2 * (q.LRpad * 8 + tile_o * q.dy_ostride + tile_c * q.x_cstride)) * 2;
         if (q.lds_bytes > lds_budget) return false;
         q.lds_bytes = max(q.lds_bytes, red_bytes); // the cross-wave sum reuses the staging space
