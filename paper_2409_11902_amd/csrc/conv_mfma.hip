@@ -1069,11 +1069,18 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     p.part = l.part ? (float *)((char *)ws + l.in + l.wt) : nullptr;
     // whole 2 x 2 tiles, rows a multiple of 8 pixels: the pooled map falls out of the repack
     const bool fuse = Z && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && (g.W % 8 == 0 || g.W == 4);
-    *err = launch_repack((const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total,
-                         p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
+    // Where the pooled map cannot come out of the repack anyway, X is read where it lies under the
+    // same conditions as dY in the data gradient (no channels-last copy, only the filter repack).
+    const bool direct = !fuse && g.W % 2 == 0 && (long)g.N * g.C * g.H * g.W >= 8L * g.R * g.S * g.K * g.C &&
+                        p.IPT * p.PH * ((g.W + 7) / 8) * (KC / 8) <= 512;
+    *err = launch_repack(direct ? nullptr : (const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C,
+                         p.ntaps_total, p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
     *pooled = fuse;
     if (*err != hipSuccess) return true;
-    p.in = in; p.wt = wt; p.bias = (const bf16_t *)b; p.out = (bf16_t *)Y;
+    p.in = direct ? (const bf16_t *)X : in;
+    p.nchw = direct;
+    p.KCin = g.C;
+    p.wt = wt; p.bias = (const bf16_t *)b; p.out = (bf16_t *)Y;
     *err = run_gather(p, variant, st);
     return true;
 }
