@@ -49,7 +49,7 @@ constexpr int KCS = KC + 8;  // LDS elements per patch pixel: 80 bytes, an odd n
 // Blocks [0, in_blocks) do the input, the rest the filter.
 struct RepackParams {
     const bf16_t *in;
-    bf16_t *out;
+    bf16_t *out;        // null: no channels-last copy, the input blocks only form Z
     int N, C, HW, Cp, in_blocks, fast;
     int in_wpb;         // waves of an input block that take items (fast path): fewer than 4 spread a small
                         // input over more compute units, one block each
@@ -157,6 +157,7 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
             if (a == 1 && !pool) break;
+            if (!p.out) break; // only the pooled map is wanted
             bf16_t *dst = p.out + ((long)n * p.HW + px0 + a * p.Wimg) * p.Cp + cg * 8;
 #pragma unroll
             for (int px = 0; px < 8; ++px) {
@@ -1073,9 +1074,9 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     // same conditions as dY in the data gradient (no channels-last copy, only the filter repack).
     const bool direct = g.W % 2 == 0 && (long)g.N * g.C * g.H * g.W >= 8L * g.R * g.S * g.K * g.C &&
                         p.IPT * p.PH * ((g.W + 7) / 8) * (KC / 8) <= 512;
-    const bool fuse = fuse0 && !direct;
-    *err = launch_repack(direct ? nullptr : (const bf16_t *)X, in, g.N, g.C, g.H * g.W, p.KCp, (const bf16_t *)W, wt, g.K, g.C,
-                         p.ntaps_total, p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
+    const bool fuse = fuse0; // (with `direct` the repack launch forms Z without writing the channels-last copy)
+    *err = launch_repack(direct && !fuse ? nullptr : (const bf16_t *)X, direct ? nullptr : in, g.N, g.C, g.H * g.W, p.KCp,
+                         (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total, p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
     *pooled = fuse;
     if (*err != hipSuccess) return true;
     p.in = direct ? (const bf16_t *)X : in;
