@@ -175,10 +175,10 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
         const DwMfmaParams &p = plan.p;
         snprintf(buf, buf_len,
                  "dw_mfma variant=%d tile=%dx%d chunk=%dimg x %drows (LR=%d/%d SEGS=%d NZ=%d XW=%d) items dy=%d z=%d "
-                 "passes dy=%d z=%d lds=%dB chunks=%d slices=%d x %d tiles grid=%u partial=%zuB",
+                 "passes dy=%d z=%d lds=%dB chunks=%d slices=%d x %d tiles grid=%u partial=%zuB%s",
                  plan.variant, p.tile_o, p.tile_c, p.NBI, p.PR, p.LR, p.LRpad, p.SEGS, p.NZ, p.XW, p.rowitems, p.citems, p.dy_passes,
                  p.z_passes, p.lds_bytes, p.nchunks, p.nslices, p.tiles_o * p.tiles_c, plan.grid,
-                 plan.partial_bytes);
+                 plan.partial_bytes, p.dy_direct ? " dY straight into LDS" : "");
     } else if ((op == CAC_OP_FWD_AND_COMPRESS || op == CAC_OP_BWD_DATA) &&
                describe_conv_mfma(g, d->dtype, op == CAC_OP_BWD_DATA, buf, buf_len)) {
     } else if (op == CAC_OP_COMPRESS || op == CAC_OP_GRAD_COSINE) {

@@ -916,7 +916,8 @@ bool plan_with(const Geom &g, int vi, DwMfmaPlan *plan)
         // wave (one output channel / input channel each) read distinct LDS banks
         q.dy_ostride = 8 * ((q.rowitems + 1) | 1); // + one block: the dY window looks one block past a row
         q.x_cstride = 8 * (((nbi * nz + 1) * (q.XW / 8)) | 1); // + the zero slot
-        q.dy_direct = g.Q % 8 == 0 && q.rowitems == 64 && q.LDY == 64 && q.dy_passes == 8 && (q.SEGS == 1 || q.SEGS == 2 || q.SEGS == 4);
+        q.dy_direct = var.R == 3 && var.SG == 1 && var.KS == 4 && // (the kernels that exist with it: see launch_variant)
+                      g.Q % 8 == 0 && q.rowitems == 64 && q.LDY == 64 && q.dy_passes == 8 && (q.SEGS == 1 || q.SEGS == 2 || q.SEGS == 4);
         q.lds_bytes = (q.XW + 2 * (q.LRpad * 8 + tile_o * q.dy_ostride + tile_c * q.x_cstride)) * 2;
         if (q.lds_bytes > lds_budget) return false;
         q.lds_bytes = max(q.lds_bytes, red_bytes); // the cross-wave sum reuses the staging space
