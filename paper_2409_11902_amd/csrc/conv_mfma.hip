@@ -1,6 +1,6 @@
 // Forward convolution and data gradient (forward / data-gradient formulas of the
 // compression figure; neither depends on the compressed activation) as one MFMA
-// implicit GEMM over channels-last copies of their inputs.
+// implicit GEMM.
 //
 // Both are the same "gather" sum
 //   out[n, m, h, w] = bias[m] + sum_t sum_kc Wt[t][m][kc] * in[n, i*is + dh_t, j*is + dw_t, kc]
@@ -10,10 +10,14 @@
 //   data gradient, s=2: one launch per output parity class (a0, b0) with the
 //                       taps whose (a0 + pad - r) and (b0 + pad - s) are even.
 // The reduction index kc must be contiguous per pixel for the MFMA operand
-// layout, hence a channels-last repack of the input (workspace) and a repack of
-// the filter into MFMA fragment order, both padded with zeros to multiples of 16
-// (one launch, repack_kernel; the forward pass forms the 2 x 2 pooled map there
-// too where the tiles are whole).  The GEMM itself is conv_gather_kernel below.
+// layout.  In LDS it always is; on the way there the input takes one of two
+// routes: a channels-last copy in the workspace (repack_kernel) that the GEMM's
+// copy waves move in 16-byte pieces, or -- where that copy would be the larger
+// part of the repack launch -- no copy at all: the copy waves read 8 channel x
+// 8 pixel blocks of the tensor as it lies and transpose them in registers.  The
+// filter is always repacked into MFMA fragment order, padded with zeros to
+// multiples of 16 channels (same launch; the forward pass forms the 2 x 2 pooled
+// map there too where the tiles are whole).  The GEMM is conv_gather_kernel.
 #include <stdio.h>
 #include <stdlib.h>
 
