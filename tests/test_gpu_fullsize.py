@@ -80,3 +80,55 @@ def test_dw_and_compress_at_full_size(config, spec):
     want_r = oracle.conv_dw_entries(g, oracle.inflate(Zr, spec.H, spec.W, spec.k, spec.k), dYd, idx)
     err = rel_l2(got_dW.ravel()[idx], want_r)
     assert err <= 2e-4, f"dW sample (tight) rel-L2 {err:.3e}"
+
+
+def _step_layers():
+    """The benchmark's default workload plus the layer kinds whose forward / data-gradient launch
+    differs in kind: stride 2 (four parity classes), 1x1, rows of 28 and 14 pixels (no pooled map
+    from the repack), a deep layer on 7x7 maps."""
+    cfg = synth.configs()
+    picks = [("cfg2_resnet18_cifar", s) for s in cfg["cfg2_resnet18_cifar"]]
+    k2 = cfg["cfg4_resnet18_imagenet_k2"]
+    picks += [("cfg4_resnet18_imagenet_k2", k2[i]) for i in (1, 2, 3, 6, 9)]
+    return picks
+
+
+STEP_LAYERS = _step_layers()
+
+
+@pytest.mark.parametrize("config,spec", STEP_LAYERS, ids=[f"{c.split('_')[0]}-{s.name}" for c, s in STEP_LAYERS])
+def test_forward_and_data_gradient_at_full_size(config, spec):
+    """Y (with bias), the Z the forward call leaves, and dX at the benchmark's sizes: sampled
+    outputs against the oracle's entry-by-entry sums, Z against the stand-alone kernel bit for bit."""
+    import torch
+    from gpu_util import Guarded, download, tdtype, upload, workspace
+    from paper_2409_11902_amd import binding as B
+
+    print(f"layer {config} {spec.name}", flush=True)
+    t = synth.make_inputs(spec, config)
+    rng = np.random.Generator(np.random.Philox(key=7))
+    t["b"] = synth.to_storage(0.1 * rng.standard_normal((spec.K,), dtype=np.float32), spec.dtype)  # (the recipe's bias is zero)
+    d = B.desc_from_spec(spec)
+    g = geom(spec)
+    hp, wp, zb, xb = B.cac_pooled_shape(d)
+    X, Wt, b, dY = (upload(t[k], spec.dtype) for k in ("X", "W", "b", "dY"))
+    Y = Guarded((spec.N, spec.K, g.P, g.Q), tdtype(spec))
+    Z = Guarded((spec.N, spec.C, hp, wp), tdtype(spec))
+    dX = Guarded((spec.N, spec.C, spec.H, spec.W), tdtype(spec))
+    Z2 = torch.empty_like(Z.t)
+    B.conv_fwd_and_compress(d, X, Wt, b, Y.t, Z.t, workspace(d, B.OP_FWD_AND_COMPRESS))
+    B.conv_bwd_data(d, Wt, dY, dX.t, workspace(d, B.OP_BWD_DATA))
+    B.cac_compress(d, X, Z2)
+    torch.cuda.synchronize()
+    for name, buf in (("Y", Y), ("Z", Z), ("dX", dX)):
+        buf.check(name)
+    assert torch.equal(Z.t.view(torch.int16), Z2.view(torch.int16))
+    got_Y, got_dX = download(Y.t), download(dX.t)
+    assert np.isfinite(got_Y).all() and np.isfinite(got_dX).all()
+    Xd, Wd, bd, dYd = (t[k].astype(np.float64) for k in ("X", "W", "b", "dY"))
+    idx = np.unique(rng.integers(0, got_Y.size, N_SAMPLES))
+    err = rel_l2(got_Y.ravel()[idx], oracle.conv_fwd_entries(g, Xd, Wd, bd, idx))
+    assert err <= 2e-2, f"Y sample rel-L2 {err:.3e}"
+    idx = np.unique(rng.integers(0, got_dX.size, N_SAMPLES))
+    err = rel_l2(got_dX.ravel()[idx], oracle.conv_dx_entries(g, Wd, dYd, idx))
+    assert err <= 2e-2, f"dX sample rel-L2 {err:.3e}"
