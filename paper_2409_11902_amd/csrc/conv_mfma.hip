@@ -597,9 +597,19 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                         wr[q % D][mi] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, wl[q2 >> 1], so + mi * kFrag, 0);
                     // Pin the order LDS reads, MFMAs, refill, and keep the instruction scheduler from
                     // moving anything to another step (it would sink the loads towards their uses).
-                    if (q + DB - 1 < STEPS) __builtin_amdgcn_sched_group_barrier(0x100, NI, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x020, MI, 0);
+                    // one LDS read or one filter load after each MFMA, in its shadow
+                    if (q + DB - 1 < STEPS) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, NI - 1, 0);
+                    } else {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - 3, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, MI - 1, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             } else
