@@ -19,6 +19,7 @@ from .cac_oracle import (  # noqa: F401
     conv_fwd_entries,
     cosine,
     inflate,
+    maxpool,
     num_threads,
     out_shape,
     pooled_shape,

@@ -100,6 +100,38 @@ void oracle_avgpool(const double *X, int64_t N, int64_t C, int64_t H, int64_t W,
     }
 }
 
+/* Compression with the tile maximum instead of the mean.  The compression section
+ * says other forms of pooling are feasible without defining one; the reading taken
+ * here: same tiles, same edge modes, Z = the largest of the elements a tile really
+ * has; inflation is oracle_inflate unchanged (the maximum repeated over its tile). */
+void oracle_maxpool(const double *X, int64_t N, int64_t C, int64_t H, int64_t W,
+                    int64_t kh, int64_t kw, int edge_mode, double *Z)
+{
+    int64_t Hp, Wp;
+    oracle_pooled_shape(H, W, kh, kw, edge_mode, &Hp, &Wp);
+    int64_t planes = N * C;
+#pragma omp parallel for schedule(static)
+    for (int64_t pl = 0; pl < planes; ++pl) {
+        const double *x = X + pl * H * W;
+        double *z = Z + pl * Hp * Wp;
+        for (int64_t i = 0; i < Hp; ++i) {
+            for (int64_t j = 0; j < Wp; ++j) {
+                double best = x[i * kh * W + j * kw]; /* a tile's first element always exists */
+                for (int64_t a = 0; a < kh; ++a) {
+                    int64_t h = i * kh + a;
+                    if (h >= H) continue;
+                    for (int64_t bcol = 0; bcol < kw; ++bcol) {
+                        int64_t w = j * kw + bcol;
+                        if (w >= W) continue;
+                        if (x[h * W + w] > best) best = x[h * W + w];
+                    }
+                }
+                z[i * Wp + j] = best;
+            }
+        }
+    }
+}
+
 /* Decompression: inflate Z back to H x W by replicating every pooled value over
  * its tile (compression figure caption: "inflate ... back to the original
  * dimensions"). */

@@ -112,6 +112,18 @@ def avgpool(X, kh: int, kw: int, edge_mode: int = EDGE_CEIL_VALID) -> np.ndarray
     return Z
 
 
+def maxpool(X, kh: int, kw: int, edge_mode: int = EDGE_CEIL_VALID) -> np.ndarray:
+    """Tile maxima over the same tiles as avgpool (a reading: the compression section names other
+    poolings as feasible and defines none)."""
+    X = _f64(X)
+    N, C, H, W = X.shape
+    hp, wp = pooled_shape(H, W, kh, kw, edge_mode)
+    Z = np.empty((N, C, hp, wp), dtype=np.float64)
+    _load().oracle_maxpool(_d(X), _i64(N), _i64(C), _i64(H), _i64(W), _i64(kh), _i64(kw),
+                           ctypes.c_int(edge_mode), _d(Z))
+    return Z
+
+
 def inflate(Z, H: int, W: int, kh: int, kw: int, edge_mode: int = EDGE_CEIL_VALID) -> np.ndarray:
     Z = _f64(Z)
     N, C, hp, wp = Z.shape
