@@ -40,7 +40,7 @@
 extern "C" {
 #endif
 
-#define CAC_VERSION 100 /* major*10000 + minor*100 + patch */
+#define CAC_VERSION 200 /* major*10000 + minor*100 + patch */
 
 typedef enum cac_status {
     CAC_OK = 0,
@@ -65,6 +65,14 @@ typedef enum cac_layout { CAC_NCHW = 0, CAC_NHWC = 1 /* not implemented: CAC_ERR
  *                dropped rows inflate to. */
 typedef enum cac_edge_mode { CAC_EDGE_CEIL_VALID = 0, CAC_EDGE_FLOOR_DROP = 1 } cac_edge_mode;
 
+/* What a pooling tile is reduced to.  The paper's experiments use the mean; its
+ * compression section names other forms of pooling as feasible without defining
+ * one.  MAX is this library's reading of that remark: Z = the largest element the
+ * tile really has (same tiles and edge modes as the mean; stored exactly, a
+ * maximum needs no rounding), and the backward pass inflates Z in the same way.
+ * Inputs are taken to be free of NaN. */
+typedef enum cac_pool_mode { CAC_POOL_MEAN = 0, CAC_POOL_MAX = 1 } cac_pool_mode;
+
 typedef enum cac_op {
     CAC_OP_FWD_AND_COMPRESS = 0,
     CAC_OP_BWD_WEIGHT_COMPRESSED = 1,
@@ -85,13 +93,15 @@ typedef struct cac_desc {
     int32_t R, S;                /* filter extent */
     int32_t stride_h, stride_w;
     int32_t pad_h, pad_w;        /* zero padding on each side */
-    int32_t pool_kh, pool_kw;    /* pooling tile; 1,1 = keep X uncompressed */
+    int32_t pool_kh, pool_kw;    /* pooling tile, any positive extents (the tiled kernels cover
+                                    1, 2, 4 and 8; others run on the plain ones); 1,1 = keep X */
     int32_t edge_mode;           /* cac_edge_mode */
     int32_t dtype;               /* cac_dtype */
     int32_t layout;              /* cac_layout */
     int32_t has_bias;            /* forward adds b[C_out] when non-zero */
     int32_t deterministic;       /* non-zero: fixed summation order in the split
                                     weight-gradient reduction (the only mode built) */
+    int32_t pool_mode;           /* cac_pool_mode */
 } cac_desc;
 
 int cac_version(void);

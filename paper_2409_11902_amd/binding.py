@@ -21,6 +21,7 @@ ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_ALIGNMENT, ERR_LA
 F32, BF16 = 0, 1
 NCHW, NHWC = 0, 1
 EDGE_CEIL_VALID, EDGE_FLOOR_DROP = 0, 1
+POOL_MEAN, POOL_MAX = 0, 1
 OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS, OP_GRAD_COSINE = range(6)
 
 EXPORTS = (
@@ -33,7 +34,7 @@ class cac_desc(ctypes.Structure):
     _fields_ = [("size", ctypes.c_uint32)] + [
         (n, ctypes.c_int32) for n in (
             "N", "C_in", "C_out", "H", "W", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w",
-            "pool_kh", "pool_kw", "edge_mode", "dtype", "layout", "has_bias", "deterministic")
+            "pool_kh", "pool_kw", "edge_mode", "dtype", "layout", "has_bias", "deterministic", "pool_mode")
     ]
 
 
@@ -83,9 +84,10 @@ def _check(rc: int):
 
 
 def make_desc(N, C_in, C_out, H, W, R, S, stride_h=1, stride_w=1, pad_h=0, pad_w=0, pool_kh=2, pool_kw=2,
-              edge_mode=EDGE_CEIL_VALID, dtype=BF16, layout=NCHW, has_bias=1, deterministic=1) -> cac_desc:
+              edge_mode=EDGE_CEIL_VALID, dtype=BF16, layout=NCHW, has_bias=1, deterministic=1,
+              pool_mode=POOL_MEAN) -> cac_desc:
     return cac_desc(ctypes.sizeof(cac_desc), N, C_in, C_out, H, W, R, S, stride_h, stride_w, pad_h, pad_w,
-                    pool_kh, pool_kw, edge_mode, dtype, layout, has_bias, deterministic)
+                    pool_kh, pool_kw, edge_mode, dtype, layout, has_bias, deterministic, pool_mode)
 
 
 def desc_from_spec(spec: synth.LayerSpec, has_bias: int = 1, **over) -> cac_desc:

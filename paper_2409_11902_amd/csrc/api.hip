@@ -42,6 +42,8 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
         return fail(CAC_ERR_INVALID_ARG, "unknown layout %d", d->layout);
     if (d->edge_mode != CAC_EDGE_CEIL_VALID && d->edge_mode != CAC_EDGE_FLOOR_DROP)
         return fail(CAC_ERR_INVALID_ARG, "unknown edge_mode %d", d->edge_mode);
+    if (d->pool_mode != CAC_POOL_MEAN && d->pool_mode != CAC_POOL_MAX)
+        return fail(CAC_ERR_INVALID_ARG, "unknown pool_mode %d", d->pool_mode);
     if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S)
         return fail(CAC_ERR_INVALID_ARG, "filter larger than the padded input");
     bool floor_mode = d->edge_mode == CAC_EDGE_FLOOR_DROP;
@@ -53,6 +55,7 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
     g->P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
     g->Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
     g->kh = d->pool_kh; g->kw = d->pool_kw;
+    g->pmax = d->pool_mode == CAC_POOL_MAX;
     g->Hp = floor_mode ? d->H / d->pool_kh : (d->H + d->pool_kh - 1) / d->pool_kh;
     g->Wp = floor_mode ? d->W / d->pool_kw : (d->W + d->pool_kw - 1) / d->pool_kw;
 

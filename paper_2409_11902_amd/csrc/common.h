@@ -16,6 +16,7 @@ struct Geom {
     int P, Q;           // output extent
     int kh, kw;         // pooling tile
     int Hp, Wp;         // pooled extent (ceil)
+    int pmax;           // non-zero: a tile is reduced to its maximum instead of its mean
 };
 
 typedef uint16_t bf16_t; // raw bfloat16 bits

@@ -1,6 +1,7 @@
 // Activation compression: Z = average pooling of X over non-overlapping,
 // origin-aligned kh x kw tiles (compression section; the compression figure
-// shows the tiling).  Bandwidth-bound: every element of X is read once with
+// shows the tiling); on request the tile maximum instead (the same section names
+// other poolings as feasible).  Bandwidth-bound: every element of X is read once with
 // 16-byte loads, every element of Z written once; no LDS.
 //
 // A thread owns one "chunk": 16 bytes of kh consecutive input rows (8 bfloat16
@@ -92,13 +93,16 @@ __global__ void __launch_bounds__(256) compress_kernel(Geom g, const T *__restri
 #pragma unroll
     for (int o = 0; o < OPC; ++o) {
         const int cols = min(KW, g.W - (w0 + o * KW)); // < 1 for pooled columns that do not exist
-        float sum = 0.f;
+        float sum = 0.f, best = v[0][o * KW]; // (a pooled column that exists has its first element)
 #pragma unroll
         for (int a = 0; a < KH; ++a)
 #pragma unroll
             for (int b = 0; b < KW; ++b)
-                if (a < rows && b < cols) sum += v[a][o * KW + b];
-        res[o] = cols == KW ? sum * inv_full : sum / (float)(rows * max(cols, 1));
+                if (a < rows && b < cols) {
+                    sum += v[a][o * KW + b];
+                    best = fmaxf(best, v[a][o * KW + b]);
+                }
+        res[o] = g.pmax ? best : cols == KW ? sum * inv_full : sum / (float)(rows * max(cols, 1));
     }
     if (g.Wp % OPC == 0) {
         // whole chunks only, and the row of Z starts on a multiple of OPC elements: one store

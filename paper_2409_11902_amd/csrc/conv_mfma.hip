@@ -1083,7 +1083,7 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     bf16_t *in = (bf16_t *)ws, *wt = (bf16_t *)((char *)ws + l.in);
     p.part = l.part ? (float *)((char *)ws + l.in + l.wt) : nullptr;
     // whole 2 x 2 tiles, rows a multiple of 8 pixels: the pooled map falls out of the repack
-    const bool fuse0 = Z && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && (g.W % 8 == 0 || g.W == 4);
+    const bool fuse0 = Z && !g.pmax && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && (g.W % 8 == 0 || g.W == 4);
     // Where the pooled map cannot come out of the repack anyway, X is read where it lies under the
     // same conditions as dY in the data gradient (no channels-last copy, only the filter repack).
     const bool direct = g.W % 2 == 0 && (long)g.N * g.C * g.H * g.W >= 8L * g.R * g.S * g.K * g.C &&

@@ -28,7 +28,8 @@ __device__ __forceinline__ float block_sum(float v, float *lds4)
     return lds4[0] + lds4[1] + lds4[2] + lds4[3];
 }
 
-// Z[n,c,i,j] = mean over the valid part of tile (i,j) of X[n,c] (compression section).
+// Z[n,c,i,j] = mean (or, for the maximum reading of "other forms of pooling", the largest
+// element) over the valid part of tile (i,j) of X[n,c] (compression section).
 template <typename T>
 __global__ void __launch_bounds__(kThreads) compress_generic(Geom g, const T *__restrict__ X, T *__restrict__ Z)
 {
@@ -42,11 +43,15 @@ __global__ void __launch_bounds__(kThreads) compress_generic(Geom g, const T *__
     const T *x = X + plane * g.H * g.W;
     int h0 = i * g.kh, w0 = j * g.kw;
     int h1 = min(h0 + g.kh, g.H), w1 = min(w0 + g.kw, g.W);
-    float sum = 0.f;
+    float sum = 0.f, best = Elem<T>::load(x + h0 * g.W + w0);
     for (int h = h0; h < h1; ++h)
-        for (int w = w0; w < w1; ++w) sum += Elem<T>::load(x + h * g.W + w);
+        for (int w = w0; w < w1; ++w) {
+            const float v = Elem<T>::load(x + h * g.W + w);
+            sum += v;
+            best = fmaxf(best, v);
+        }
     float cnt = (float)((h1 - h0) * (w1 - w0));
-    Elem<T>::store(Z + idx, sum / cnt);
+    Elem<T>::store(Z + idx, g.pmax ? best : sum / cnt);
 }
 
 // Y = X * W + b (forward formula of the compression figure).

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert B.cac_version() == 100
+    assert B.cac_version() == 200
 
 
 def test_desc_layout_matches_header():
@@ -40,12 +40,13 @@ def test_desc_layout_matches_header():
 
 
 @pytest.mark.parametrize("hw", [(56, 56), (28, 28), (14, 14), (7, 7), (5, 9), (224, 224)])
-@pytest.mark.parametrize("k", [(1, 1), (2, 2), (4, 4), (2, 4)])
+@pytest.mark.parametrize("k", [(1, 1), (2, 2), (4, 4), (2, 4), (3, 3), (5, 3)])
 @pytest.mark.parametrize("mode", [B.EDGE_CEIL_VALID, B.EDGE_FLOOR_DROP])
 def test_pooled_shape_bit_exact_vs_oracle(hw, k, mode):
     H, W = hw
     for dtype, eb in ((B.F32, 4), (B.BF16, 2)):
-        d = B.make_desc(32, 64, 64, H, W, 3, 3, 1, 1, 1, 1, k[0], k[1], edge_mode=mode, dtype=dtype)
+        d = B.make_desc(32, 64, 64, H, W, 3, 3, 1, 1, 1, 1, k[0], k[1], edge_mode=mode, dtype=dtype,
+                        pool_mode=B.POOL_MAX if dtype == B.BF16 else B.POOL_MEAN)   # the shape does not depend on it
         hp, wp, zb, xb = B.cac_pooled_shape(d)
         assert (hp, wp) == oracle.pooled_shape(H, W, k[0], k[1], mode)
         assert (xb, zb) == oracle.saved_bytes(32, 64, H, W, k[0], k[1], eb, mode)
@@ -91,7 +92,8 @@ def _expect(code, fn, *a):
 def test_invalid_descriptors_are_rejected():
     good = dict(N=2, C_in=4, C_out=4, H=8, W=8, R=3, S=3, pad_h=1, pad_w=1)
     for bad in (dict(N=0), dict(C_in=-1), dict(H=0), dict(R=0), dict(stride_h=0), dict(pad_w=-1),
-                dict(pool_kh=0), dict(dtype=7), dict(layout=5), dict(edge_mode=3), dict(R=11, pad_h=0)):
+                dict(pool_kh=0), dict(dtype=7), dict(layout=5), dict(edge_mode=3), dict(pool_mode=2), dict(pool_mode=-1),
+                dict(R=11, pad_h=0)):
         d = B.make_desc(**{**good, **bad})
         _expect(B.ERR_INVALID_ARG, B.cac_pooled_shape, d)
     d = B.make_desc(**good)
