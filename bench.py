@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--layers", default="", help="comma-separated layer indices of the workload (default all)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-backward", action="store_true",
+                    help="the step calls conv_bwd_weight_compressed and conv_bwd_data instead of conv_bwd_weight_and_data")
     ap.add_argument("--only", default="", choices=["", "dw", "compress", "fwd", "dx", "copy"],
                     help="profiling aid: run just this entry point --steps times per layer and exit "
                          "(copy: a plain 256 MiB device copy, the yardstick the HBM counters are scaled by)")
@@ -57,7 +59,8 @@ class Layer:
         td = torch.float32 if spec.dtype == synth.F32 else torch.bfloat16
         dev = "cuda:0"
         self.ws = {}
-        ops = (B.OP_BWD_WEIGHT_COMPRESSED,) if dw_only else (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA)
+        ops = (B.OP_BWD_WEIGHT_COMPRESSED,) if dw_only else (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA,
+                                                              B.OP_BWD_WEIGHT_AND_DATA)
         for op in ops:
             n = B.cac_workspace_size(self.d, op)
             self.ws[op] = torch.empty(max(n, 16), dtype=torch.uint8, device=dev) if n else None
@@ -143,8 +146,12 @@ def main():
     def step():
         for L in layers:
             B.conv_fwd_and_compress(L.d, L.X, L.W, L.b, L.Y, L.Z, L.ws[B.OP_FWD_AND_COMPRESS], stream)
-            B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], stream)
-            B.conv_bwd_data(L.d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], stream)
+            if args.separate_backward:
+                B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], stream)
+                B.conv_bwd_data(L.d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], stream)
+            else:
+                # both gradients of the layer in one call (same kernels and results; one launch fewer)
+                B.conv_bwd_weight_and_data(L.d, L.Z, L.W, L.dY, L.dW, L.dX, L.ws[B.OP_BWD_WEIGHT_AND_DATA], stream)
 
     # ---- untimed warm-up (also sets kernel attributes before any capture)
     for _ in range(max(1, args.warmup)):
@@ -281,7 +288,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if specs[0].dtype == synth.BF16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": [L.spec.name for L in layers], "batch": specs[0].N,
-                   "pool_k": specs[0].k, "launch": "hip_graph" if graph is not None else "eager"},
+                   "pool_k": specs[0].k, "launch": "hip_graph" if graph is not None else "eager",
+                   "backward": "two calls" if args.separate_backward else "conv_bwd_weight_and_data"},
         "dw_tflops": round(dw_tflops, 1), "dw_frac_of_bf16_peak": round(dw_tflops / PEAK_BF16_TFLOPS, 4),
         "compress_cold_gbps": round(comp_cold_gbps, 1), "compress_frac_of_hbm_peak": round(comp_cold_gbps / PEAK_HBM_GBPS, 4),
         "activation_bytes": {"x": x_total, "z": z_total, "saved": x_total - z_total, "ratio": round(x_total / z_total, 3)},

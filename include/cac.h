@@ -79,7 +79,8 @@ typedef enum cac_op {
     CAC_OP_BWD_DATA = 2,
     CAC_OP_COMPRESS = 3,
     CAC_OP_BWD_BIAS = 4,
-    CAC_OP_GRAD_COSINE = 5
+    CAC_OP_GRAD_COSINE = 5,
+    CAC_OP_BWD_WEIGHT_AND_DATA = 6
 } cac_op;
 
 /* One convolution layer with a compressed saved input.  Plain data, filled by
@@ -151,6 +152,17 @@ int conv_bwd_weight_compressed(const cac_desc *d, const void *Z, const void *dY,
  * dX [N][C_in][H][W] is overwritten. */
 int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX,
                   void *ws, size_t ws_bytes, void *stream);
+
+/* Both gradients of a layer in one call: exactly the results of
+ * conv_bwd_weight_compressed followed by conv_bwd_data (same kernels, same
+ * summation orders, bit-identical outputs), with the small launches of the two
+ * shared where they are independent -- the sum over the weight gradient's pixel
+ * slices runs in the launch that repacks the data gradient's operands.  A
+ * backward pass that needs both (the usual case; the gradient formulas of the
+ * compression figure) saves a launch per layer.  `ws` needs
+ * cac_workspace_size(CAC_OP_BWD_WEIGHT_AND_DATA) bytes. */
+int conv_bwd_weight_and_data(const cac_desc *d, const void *Z, const void *W, const void *dY, void *dW,
+                             void *dX, void *ws, size_t ws_bytes, void *stream);
 
 /* Bias gradient (bias-gradient formula in the same figure): db[o] = sum_{n,p,q} dY.
  * db [C_out] float is overwritten. */

@@ -22,11 +22,13 @@ F32, BF16 = 0, 1
 NCHW, NHWC = 0, 1
 EDGE_CEIL_VALID, EDGE_FLOOR_DROP = 0, 1
 POOL_MEAN, POOL_MAX = 0, 1
-OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS, OP_GRAD_COSINE = range(6)
+(OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS, OP_GRAD_COSINE,
+ OP_BWD_WEIGHT_AND_DATA) = range(7)
 
 EXPORTS = (
     "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size", "cac_describe_plan",
     "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias", "cac_grad_cosine",
+    "conv_bwd_weight_and_data",
 )
 
 
@@ -165,6 +167,12 @@ def conv_bwd_weight_compressed(d, Z, dY, dW, ws=None, stream=None):
 def conv_bwd_data(d, W, dY, dX, ws=None, stream=None):
     wp, wb = _ws(ws)
     _check(lib().conv_bwd_data(ctypes.byref(d), _ptr(W), _ptr(dY), _ptr(dX), wp, wb, _stream(stream)))
+
+
+def conv_bwd_weight_and_data(d, Z, W, dY, dW, dX, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().conv_bwd_weight_and_data(ctypes.byref(d), _ptr(Z), _ptr(W), _ptr(dY), _ptr(dW), _ptr(dX), wp, wb,
+                                          _stream(stream)))
 
 
 def conv_bwd_bias(d, dY, db, stream=None):

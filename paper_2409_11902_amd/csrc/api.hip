@@ -90,6 +90,15 @@ static int launched(hipError_t e, const char *what)
     return CAC_OK;
 }
 
+static size_t workspace_bytes(const Geom &g, int dtype, int op);
+
+// Part of the combined backward call's workspace that the weight gradient uses (the data
+// gradient's part starts behind it, 256-byte aligned).
+static size_t both_dw_bytes(const Geom &g, int dtype)
+{
+    return (workspace_bytes(g, dtype, CAC_OP_BWD_WEIGHT_COMPRESSED) + 255) & ~(size_t)255;
+}
+
 static size_t workspace_bytes(const Geom &g, int dtype, int op)
 {
     if (op == CAC_OP_BWD_WEIGHT_COMPRESSED) {
@@ -100,6 +109,9 @@ static size_t workspace_bytes(const Geom &g, int dtype, int op)
     if (op == CAC_OP_FWD_AND_COMPRESS) return conv_mfma_workspace(g, dtype, false);
     if (op == CAC_OP_BWD_DATA) return conv_mfma_workspace(g, dtype, true);
     if (op == CAC_OP_GRAD_COSINE) return cosine_workspace((long)g.K * g.C * g.R * g.S);
+    // both gradients in one call: the partial sums are still being read when the repacks are written
+    if (op == CAC_OP_BWD_WEIGHT_AND_DATA)
+        return both_dw_bytes(g, dtype) + workspace_bytes(g, dtype, CAC_OP_BWD_DATA);
     return 0;
 }
 
@@ -160,7 +172,7 @@ int cac_workspace_size(const cac_desc *d, int op, size_t *bytes)
     Geom g;
     int rc = make_geom(d, &g, true);
     if (rc) return rc;
-    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_GRAD_COSINE) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_WEIGHT_AND_DATA) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     if (!bytes) return fail(CAC_ERR_INVALID_ARG, "bytes is NULL");
     *bytes = workspace_bytes(g, d->dtype, op);
     return CAC_OK;
@@ -172,7 +184,7 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
     int rc = make_geom(d, &g, true);
     if (rc) return rc;
     if (!buf || buf_len == 0) return fail(CAC_ERR_INVALID_ARG, "buf is NULL or empty");
-    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_GRAD_COSINE) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_WEIGHT_AND_DATA) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     DwMfmaPlan plan;
     if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && dw_mfma_plan(g, d->dtype, &plan)) {
         const DwMfmaParams &p = plan.p;
@@ -186,6 +198,11 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
                describe_conv_mfma(g, d->dtype, op == CAC_OP_BWD_DATA, buf, buf_len)) {
     } else if (op == CAC_OP_COMPRESS || op == CAC_OP_GRAD_COSINE) {
         snprintf(buf, buf_len, "streaming kernel");
+    } else if (op == CAC_OP_BWD_WEIGHT_AND_DATA) {
+        char dx[64];
+        const bool merged = dw_mfma_plan(g, d->dtype, &plan) && !plan.p.direct && describe_conv_mfma(g, d->dtype, true, dx, sizeof dx);
+        snprintf(buf, buf_len, merged ? "weight gradient, then its slice sum in the launch of the data gradient's repack, then the data gradient"
+                                      : "weight gradient, then data gradient, as in the separate calls");
     } else {
         snprintf(buf, buf_len, "generic kernel");
     }
@@ -246,6 +263,33 @@ int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX, vo
     hipError_t e = hipSuccess;
     if (!launch_dx_mfma(g, d->dtype, W, dY, dX, ws, (hipStream_t)stream, &e))
         e = launch_dx_generic(g, d->dtype, W, dY, dX, (hipStream_t)stream);
+    return launched(e, "data gradient");
+}
+
+int conv_bwd_weight_and_data(const cac_desc *d, const void *Z, const void *W, const void *dY, void *dW, void *dX, void *ws,
+                             size_t ws_bytes, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(Z, "Z")) || (rc = check_ptr(W, "W")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dW, "dW")) ||
+        (rc = check_ptr(dX, "dX")))
+        return rc;
+    if ((rc = check_ws(g, d->dtype, CAC_OP_BWD_WEIGHT_AND_DATA, ws, ws_bytes, nullptr))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    void *ws_dx = ws ? (char *)ws + both_dw_bytes(g, d->dtype) : nullptr;
+    DwReduceTail tail{};
+    DwMfmaPlan plan;
+    if (dw_mfma_plan(g, d->dtype, &plan))
+        rc = launched(launch_dw_mfma(plan, Z, dY, (float *)dW, ws, st, &tail), "weight gradient (MFMA)");
+    else
+        rc = launched(launch_dw_generic(g, d->dtype, Z, dY, (float *)dW, st), "weight gradient");
+    if (rc) return rc;
+    hipError_t e = hipSuccess;
+    if (!launch_dx_mfma(g, d->dtype, W, dY, dX, ws_dx, st, &e, &tail)) {
+        if ((rc = launched(launch_dw_reduce(tail, st), "weight gradient (slice sum)"))) return rc;
+        e = launch_dx_generic(g, d->dtype, W, dY, dX, st);
+    }
     return launched(e, "data gradient");
 }
 

@@ -1,6 +1,7 @@
 // Forward convolution / data gradient as an MFMA gather GEMM (see conv_mfma.hip).
 #pragma once
 #include "common.h"
+#include "dw_reduce.h"
 
 namespace cac {
 
@@ -32,6 +33,6 @@ bool describe_conv_mfma(const Geom &g, int dtype, bool data_grad, char *buf, siz
 bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, const void *b, void *Y, void *Z, void *ws,
                      hipStream_t st, hipError_t *err, bool *pooled);
 bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,
-                    hipError_t *err);
+                    hipError_t *err, const DwReduceTail *tail = nullptr);
 
 } // namespace cac

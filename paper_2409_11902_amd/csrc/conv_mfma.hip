@@ -23,6 +23,7 @@
 
 #include "common.h"
 #include "conv_mfma.h"
+#include "dw_reduce.h"
 
 namespace cac {
 
@@ -64,16 +65,16 @@ struct RepackParams {
     int O, Cw, RS, Mp, KCp, transpose;
 };
 
-__global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
+__device__ __forceinline__ void repack_body(const RepackParams &p, const int bid)
 {
     constexpr int kFilterElems = 32 * (16 * 9 + 2); // a 32 x 16 block of (o, c) pairs, 9 taps, padded rows
     __shared__ bf16_t sm[kFilterElems > 64 * 66 ? kFilterElems : 64 * 66];
-    if ((int)blockIdx.x >= p.in_blocks) {
+    if (bid >= p.in_blocks) {
         // One block per (32-row block, 16-channel block): its part of W -- for every o a contiguous
         // run of (c, tap) -- goes through LDS as it lies in memory; then every thread gathers the
         // 8 channels of one lane of one tap's fragment and writes them as 16 bytes, a wave one
         // contiguous KiB.  Rows are padded to an odd number of dwords against bank conflicts.
-        const int b = blockIdx.x - p.in_blocks;
+        const int b = bid - p.in_blocks;
         const int mblks = p.Mp / 32, kblks = p.KCp / 16, mblk = b % mblks, kblk = b / mblks;
         const int rows = p.transpose ? 16 : 32, cols = p.transpose ? 32 : 16; // o rows, c columns
         const int o0 = p.transpose ? kblk * 16 : mblk * 32, c0 = p.transpose ? mblk * 32 : kblk * 16;
@@ -135,7 +136,7 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
         const int pgs = pool ? p.HW / 16 : (p.HW + 7) / 8;     // items along the pixels (the last may be partial)
         const int cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
         if ((int)(threadIdx.x >> 6) >= p.in_wpb) return;
-        const long item = ((long)blockIdx.x * p.in_wpb + (threadIdx.x >> 6)) * 64 + (threadIdx.x & 63);
+        const long item = ((long)bid * p.in_wpb + (threadIdx.x >> 6)) * 64 + (threadIdx.x & 63);
         if (item >= (long)p.N * cgb * pgs * cgw) return;
         const int cl = item % cgw;
         long t1 = item / cgw;
@@ -227,7 +228,7 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
     }
     // block -> (image, 64-channel block, 64-pixel block)
     const int pbs = (p.HW + 63) / 64, cbs = (p.Cp + 63) / 64;
-    const int pb = blockIdx.x % pbs, t1 = blockIdx.x / pbs;
+    const int pb = bid % pbs, t1 = bid / pbs;
     const int cb = t1 % cbs, n = t1 / cbs;
     const int c0 = cb * 64, p0 = pb * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -242,10 +243,26 @@ __global__ void __launch_bounds__(256) repack_kernel(RepackParams p)
     }
 }
 
+__global__ void __launch_bounds__(256) repack_kernel(RepackParams p) { repack_body(p, blockIdx.x); }
+
+// The repacks of a data-gradient call and, in the blocks after them, the slice sum that the
+// weight gradient of the same layer has left over: two small, independent pieces of a backward
+// pass that would otherwise each pay for a launch.
+template <int SY, int V>
+__global__ void __launch_bounds__(256) repack_reduce_kernel(RepackParams p, unsigned nrep, DwReduceTail t)
+{
+    if (blockIdx.x < nrep)
+        repack_body(p, blockIdx.x);
+    else
+        dw_reduce_body<SY, V>(t.part, t.dW, t.total, t.nslices, blockIdx.x - nrep);
+}
+
 // Launches the input and filter repacks of one call.
 // Z, Wimg: see RepackParams (Z null: no pooling; else HW must be a multiple of 2*Wimg and Wimg 4 or a multiple of 8).
+// tail: a deferred weight-gradient slice sum to run in the same launch, or null.
 hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, int Cp, const bf16_t *W, bf16_t *Wt, int O,
-                         int Cw, int RS, int Mp, int KCp, int transpose, bf16_t *Z, int Wimg, hipStream_t st)
+                         int Cw, int RS, int Mp, int KCp, int transpose, bf16_t *Z, int Wimg, hipStream_t st,
+                         const DwReduceTail *tail = nullptr)
 {
     RepackParams p{};
     p.in = in; p.out = out; p.N = N; p.C = C; p.HW = HW; p.Cp = Cp;
@@ -259,7 +276,23 @@ hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, in
     p.in_wpb = items > 64 * 256 ? 4 : 1; // (measured: two waves per block are slower than either)
     p.in_blocks = p.fast ? (int)((items + 64 * p.in_wpb - 1) / (64 * p.in_wpb)) : N * ((Cp + 63) / 64) * ((HW + 63) / 64);
     p.W = W; p.Wt = Wt; p.O = O; p.Cw = Cw; p.RS = RS; p.Mp = Mp; p.KCp = KCp; p.transpose = transpose;
-    hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(p.in_blocks + (Mp / 32) * (KCp / 16))), dim3(256), 0, st, p);
+    const unsigned nrep = (unsigned)(p.in_blocks + (Mp / 32) * (KCp / 16));
+    if (tail && tail->blocks) {
+        const DwReduceTail &t = *tail;
+#define CAC_RR(SY, V) hipLaunchKernelGGL((repack_reduce_kernel<SY, V>), dim3(nrep + t.blocks), dim3(256), 0, st, p, nrep, t)
+        if (t.V == 4) {
+            if (t.SY == 16) CAC_RR(16, 4);
+            else if (t.SY == 4) CAC_RR(4, 4);
+            else CAC_RR(1, 4);
+        } else {
+            if (t.SY == 16) CAC_RR(16, 1);
+            else if (t.SY == 4) CAC_RR(4, 1);
+            else CAC_RR(1, 1);
+        }
+#undef CAC_RR
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(repack_kernel, dim3(nrep), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
@@ -1102,8 +1135,10 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
 }
 
 // Data gradient: dX = W^T * dY.  False when the geometry is not covered.
+// tail: a weight-gradient slice sum to run in the repack launch (see repack_reduce_kernel); when
+// this returns false nothing has been launched and the tail is still the caller's to run.
 bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, void *dX, void *ws, hipStream_t st,
-                    hipError_t *err)
+                    hipError_t *err, const DwReduceTail *tail)
 {
     GatherParams base{}, cls[4];
     int variant[4], ncls = 0;
@@ -1120,7 +1155,7 @@ bool launch_dx_mfma(const Geom &g, int dtype, const void *W, const void *dY, voi
     }
     const bool direct = dx_reads_in_place(g, cls, ncls);
     *err = launch_repack(direct ? nullptr : (const bf16_t *)dY, in, g.N, g.K, g.P * g.Q, base.KCp, (const bf16_t *)W, wt, g.K, g.C,
-                         base.ntaps_total, base.Mp, base.KCp, 1, nullptr, 0, st);
+                         base.ntaps_total, base.Mp, base.KCp, 1, nullptr, 0, st, tail);
     for (int k = 0; k < ncls && *err == hipSuccess; ++k) {
         cls[k].in = direct ? (const bf16_t *)dY : in;
         cls[k].nchw = direct;

@@ -1,6 +1,7 @@
 // Launch plan of the MFMA weight-gradient kernel (see dw_mfma.hip).
 #pragma once
 #include "common.h"
+#include "dw_reduce.h"
 
 namespace cac {
 
@@ -39,6 +40,7 @@ struct DwMfmaPlan {
 
 // False when the geometry is not covered (the caller then uses the generic kernel).
 bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan);
-hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY, float *dW, void *ws, hipStream_t st);
+hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY, float *dW, void *ws, hipStream_t st,
+                          DwReduceTail *defer = nullptr);
 
 } // namespace cac

@@ -37,6 +37,7 @@
 
 #include "common.h"
 #include "dw_mfma.h"
+#include "dw_reduce.h"
 
 namespace cac {
 
@@ -758,38 +759,11 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
 #undef CAC_G
 }
 
-// dW = sum over the slices of their partial sums, in slice order.  A block of 256 threads owns
-// 256/SY vectors of V floats; its SY thread rows take every SY-th slice each and are combined
-// through LDS in a fixed order, so the result does not depend on scheduling.
+// The slice sum as a launch of its own (body and description: dw_reduce.h).
 template <int SY, int V>
 __global__ void __launch_bounds__(256) dw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW, long total, int nslices)
 {
-    typedef float vec __attribute__((ext_vector_type(V)));
-    constexpr int CX = 256 / SY;
-    __shared__ vec red[SY > 1 ? SY : 1][CX];
-    const int cx = threadIdx.x % CX, sy = threadIdx.x / CX;
-    const long nvec = total / V, col = (long)blockIdx.x * CX + cx;
-    const bool valid = col < nvec;
-    const vec *src = (const vec *)part + (valid ? col : 0);
-    vec sum = 0.f;
-    int sl = sy;
-    for (; sl + 3 * SY < nslices; sl += 4 * SY) {
-        const vec a = src[(long)sl * nvec], b = src[(long)(sl + SY) * nvec];
-        const vec c = src[(long)(sl + 2 * SY) * nvec], d = src[(long)(sl + 3 * SY) * nvec];
-        sum += a;
-        sum += b;
-        sum += c;
-        sum += d;
-    }
-    for (; sl < nslices; sl += SY) sum += src[(long)sl * nvec];
-    if (SY > 1) {
-        red[sy][cx] = sum;
-        __syncthreads();
-        if (sy != 0) return;
-#pragma unroll
-        for (int k = 1; k < SY; ++k) sum += red[k][cx];
-    }
-    if (valid) ((vec *)dW)[col] = sum;
+    dw_reduce_body<SY, V>(part, dW, total, nslices, blockIdx.x);
 }
 
 uint32_t magic_of(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
@@ -1014,32 +988,43 @@ bool dw_mfma_plan(const Geom &g, int dtype, DwMfmaPlan *plan)
     return true;
 }
 
-hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY, float *dW, void *ws, hipStream_t st)
+hipError_t launch_dw_reduce(const DwReduceTail &t, hipStream_t st)
+{
+    if (!t.blocks) return hipSuccess;
+#define CAC_REDUCE(SY, V) \
+    hipLaunchKernelGGL((dw_reduce_kernel<SY, V>), dim3(t.blocks), dim3(256), 0, st, t.part, t.dW, t.total, t.nslices)
+    if (t.V == 4) {
+        if (t.SY == 16) CAC_REDUCE(16, 4);
+        else if (t.SY == 4) CAC_REDUCE(4, 4);
+        else CAC_REDUCE(1, 4);
+    } else {
+        if (t.SY == 16) CAC_REDUCE(16, 1);
+        else if (t.SY == 4) CAC_REDUCE(4, 1);
+        else CAC_REDUCE(1, 1);
+    }
+#undef CAC_REDUCE
+    return hipGetLastError();
+}
+
+// `defer`: when given, the slice sum is not launched; what it has to do is written there instead
+// (blocks = 0 when the main kernel has written dW itself) and the caller sees to it.
+hipError_t launch_dw_mfma(const DwMfmaPlan &plan, const void *Z, const void *dY, float *dW, void *ws, hipStream_t st,
+                          DwReduceTail *defer)
 {
     DwMfmaParams p = plan.p;
     p.Z = (const bf16_t *)Z;
     p.dY = (const bf16_t *)dY;
     p.out = p.direct ? dW : (float *)ws;
+    if (defer) defer->blocks = 0;
     const Variant &var = kVariants[plan.variant];
     hipError_t e = var.launch(p, dim3(plan.grid), st);
     if (e != hipSuccess || p.direct) return e;
-    const long total = (long)p.K * p.C * var.R * var.R;
-    // vectors of 4 floats when a slice is a whole number of them (every slice then starts aligned);
-    // thread rows over the slices when there are many of them
-#define CAC_REDUCE(SY, V)                                                                                              \
-    hipLaunchKernelGGL((dw_reduce_kernel<SY, V>), dim3((unsigned)((total / V + 256 / SY - 1) / (256 / SY))), dim3(256), 0, st, \
-                       (const float *)ws, dW, total, p.nslices)
-    if (total % 4 == 0) {
-        if (p.nslices >= 32) CAC_REDUCE(16, 4);
-        else if (p.nslices >= 8) CAC_REDUCE(4, 4);
-        else CAC_REDUCE(1, 4);
-    } else {
-        if (p.nslices >= 32) CAC_REDUCE(16, 1);
-        else if (p.nslices >= 8) CAC_REDUCE(4, 1);
-        else CAC_REDUCE(1, 1);
+    const DwReduceTail t = make_reduce_tail((const float *)ws, dW, (long)p.K * p.C * var.R * var.R, p.nslices);
+    if (defer) {
+        *defer = t;
+        return hipSuccess;
     }
-#undef CAC_REDUCE
-    return hipGetLastError();
+    return launch_dw_reduce(t, st);
 }
 
 } // namespace cac

@@ -132,6 +132,12 @@ def test_null_and_misaligned_pointers_fail_before_any_launch():
     assert L.conv_bwd_data(p, None, a, a, None, 0, None) == B.ERR_INVALID_ARG
     assert L.conv_bwd_bias(p, a, None, None) == B.ERR_INVALID_ARG
     assert b"NULL" in L.cac_last_error()
+    for k in range(5):
+        args = [a] * 5
+        args[k] = None
+        assert L.conv_bwd_weight_and_data(p, *args, None, 0, None) == B.ERR_INVALID_ARG
+        args[k] = m
+        assert L.conv_bwd_weight_and_data(p, *args, None, 0, None) == B.ERR_ALIGNMENT
     need = B.cac_workspace_size(d, B.OP_GRAD_COSINE)
     assert need > 0
     assert L.cac_grad_cosine(p, a, None, a, a, need, None) == B.ERR_INVALID_ARG
@@ -150,6 +156,22 @@ def test_workspace_too_small_is_reported():
         a = ctypes.c_void_p(0x1000)
         assert L.conv_bwd_weight_compressed(ctypes.byref(d), a, a, a, a, need - 1, None) == B.ERR_WORKSPACE_TOO_SMALL
         assert L.conv_bwd_weight_compressed(ctypes.byref(d), a, a, a, None, 0, None) == B.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_combined_backward_workspace_holds_both_parts():
+    L = B.lib()
+    a = ctypes.c_void_p(0x1000)
+    merged = 0
+    for layers in synth.configs().values():
+        for spec in layers:
+            d = B.desc_from_spec(spec)
+            dw, dx = B.cac_workspace_size(d, B.OP_BWD_WEIGHT_COMPRESSED), B.cac_workspace_size(d, B.OP_BWD_DATA)
+            both = B.cac_workspace_size(d, B.OP_BWD_WEIGHT_AND_DATA)
+            assert both == (dw + 255) // 256 * 256 + dx
+            if both:
+                assert L.conv_bwd_weight_and_data(ctypes.byref(d), a, a, a, a, a, a, ctypes.c_size_t(both - 1), None) == B.ERR_WORKSPACE_TOO_SMALL
+            merged += "in the launch of" in B.cac_describe_plan(d, B.OP_BWD_WEIGHT_AND_DATA)
+    assert merged >= 20      # most bf16 layers split their pixels and share the launch
 
 
 def test_every_bf16_layer_of_the_configs_has_an_mfma_weight_gradient_plan():
