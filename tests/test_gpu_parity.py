@@ -89,6 +89,11 @@ SMALL = [
     ("s2 parity classes", 3, 32, 48, 16, 16, 3, 3, 2, 1, 2),
     ("1x1 wide", 2, 128, 64, 14, 14, 1, 1, 1, 0, 2),
     ("1x1 s2 wide", 2, 96, 160, 14, 14, 1, 1, 2, 0, 4),
+    # 1x1 stride 2 on even maps: three of the four parity classes of the data gradient have no taps
+    ("1x1 s2 even grid", 3, 40, 24, 12, 12, 1, 1, 2, 0, 2),
+    ("1x1 s2 even grid wide", 2, 64, 128, 16, 24, 1, 1, 2, 0, 2),
+    ("1x1 s2 even grid 5 img", 5, 32, 32, 8, 8, 1, 1, 2, 0, 2),
+    ("1x1 s2 rows of 6", 2, 32, 64, 12, 6, 1, 1, 2, 0, 2),
     # deep layers on tiny maps: forward and data gradient share a tile's channel blocks out over
     # several workgroups (float partial sums + a finishing pass); 160 channels = 5 blocks
     ("4x4 maps deep", 4, 256, 128, 4, 4, 3, 3, 1, 1, 2),
@@ -257,7 +262,8 @@ def test_pooling_fused_into_the_forward_pass_equals_the_standalone_kernel(shape)
     assert np.abs(Z2.float().cpu().numpy() - want).max() <= np.abs(want).max() * 2.0 ** -8
 
 
-def test_graph_capture_and_side_stream():
+@pytest.mark.parametrize("combined", [False, True], ids=["separate backward calls", "combined backward call"])
+def test_graph_capture_and_side_stream(combined):
     """The three calls enqueue on the caller's stream only and record no memset nodes: captured
     in a HIP graph on a side stream and replayed several times, with eager work and
     synchronisations in between, every replay reproduces the eager result."""
@@ -274,12 +280,16 @@ def test_graph_capture_and_side_stream():
     Z = torch.empty((spec.N, spec.C, hp, wp), dtype=bf, device="cuda:0")
     dW = torch.empty((spec.K, spec.C, 3, 3), dtype=torch.float32, device="cuda:0")
     dX = torch.empty((spec.N, spec.C, spec.H, spec.W), dtype=bf, device="cuda:0")
-    ws = [workspace(d, op) for op in (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA)]
+    ws = [workspace(d, op) for op in (B.OP_FWD_AND_COMPRESS, B.OP_BWD_WEIGHT_COMPRESSED, B.OP_BWD_DATA,
+                                      B.OP_BWD_WEIGHT_AND_DATA)]
 
     def step(stream):
         B.conv_fwd_and_compress(d, X, Wt, b, Y, Z, ws[0], stream)
-        B.conv_bwd_weight_compressed(d, Z, dY, dW, ws[1], stream)
-        B.conv_bwd_data(d, Wt, dY, dX, ws[2], stream)
+        if combined:
+            B.conv_bwd_weight_and_data(d, Z, Wt, dY, dW, dX, ws[3], stream)
+        else:
+            B.conv_bwd_weight_compressed(d, Z, dY, dW, ws[1], stream)
+            B.conv_bwd_data(d, Wt, dY, dX, ws[2], stream)
 
     outs = (Y, Z, dW, dX)
     step(torch.cuda.current_stream())
