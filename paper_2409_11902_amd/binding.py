@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.cac_compress.argtypes = [dp, vp, vp, vp]
         L.conv_bwd_weight_compressed.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_data.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.conv_bwd_weight_and_data.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_bias.argtypes = [dp, vp, vp, vp]
         L.cac_grad_cosine.argtypes = [dp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         for n in EXPORTS[2:]:
@@ -127,7 +128,7 @@ def cac_workspace_size(d: cac_desc, op: int) -> int:
 
 
 def cac_describe_plan(d: cac_desc, op: int) -> str:
-    buf = ctypes.create_string_buffer(512)
+    buf = ctypes.create_string_buffer(2048)
     _check(lib().cac_describe_plan(ctypes.byref(d), op, buf, len(buf)))
     return buf.value.decode()
 
