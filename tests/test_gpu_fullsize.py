@@ -90,6 +90,13 @@ def _step_layers():
     picks = [("cfg2_resnet18_cifar", s) for s in cfg["cfg2_resnet18_cifar"]]
     k2 = cfg["cfg4_resnet18_imagenet_k2"]
     picks += [("cfg4_resnet18_imagenet_k2", k2[i]) for i in (1, 2, 3, 6, 9)]
+    picks += [("cfg5_deep_small_spatial", s) for s in cfg["cfg5_deep_small_spatial"]]
+    # the bottleneck blocks' layer kinds: narrow and wide 1x1, a stride-2 1x1 shortcut, stride-2 3x3,
+    # thousands of channels on 7x7 maps (odd planes: the element-wise repack)
+    c3 = {s.name: s for s in cfg["cfg3_resnet50_imagenet"]}
+    for name in ("s1.b0.1x1_64_256@56", "s1.b1.1x1_256_64@56", "s2.b0.3x3s2_128_128@56", "s3.b0.down1x1s2_512_1024@28",
+                 "s3.b1.1x1_1024_256@14", "s4.b0.1x1_512_2048@7", "s4.b1.1x1_2048_512@7"):
+        picks.append(("cfg3_resnet50_imagenet", c3[name]))
     return picks
 
 
