@@ -22,6 +22,8 @@ struct GatherParams {
     int IPT, patch_px;  // images per pixel tile; patch pixels of the whole tile
     int tiles_per_img, ngrp, gpw, nkb; // tiles per image; image groups; groups per workgroup; channel blocks
     int ksplit, kbs;    // workgroups sharing one tile's channel blocks (grid z); channel blocks of each
+    int T, t_log2, kcs; // 32-channel groups staged per pass (1, 2 or 4; more than one only where taps * T is 4 or 8);
+                        // LDS elements per patch pixel (32 * T + 8); a "channel block" above is 32 * T channels
     int nchw, KCin;     // the kernel reads the input in its own layout (KCin channels) instead of a channels-last copy
     int wide_store;     // the epilogue writes 16-byte runs of 8 pixels (whole planes, a multiple of 8 pixels each)
     uint32_t m_wc, m_ppi, m_pwd, m_kbs, m_img; // division magics of Wc, Hc*Wc, PWd, kbs, PH*PWd

@@ -328,14 +328,19 @@ constexpr uint32_t kNoElem = 0x40000000u;
 // a lane then owns runs of 4 consecutive pixels.  Used when consecutive pixels of the launch are
 // consecutive and 8-byte aligned in memory; the runs leave as 8-byte stores, or, with
 // p.wide_store, through LDS as 16-byte stores that cover whole rows.
-// DEEP: nine taps; the operand rings described at their declaration.
-template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS, bool NCHW>
+// NTT: taps x 32-channel groups of a pass when that is 9 (nine taps, one group), 8 or 4: the operand
+// rings described at their declaration; 0: any number of taps, one group, a shallow prefetch.
+template <int NI, int WM, int WN, bool TR, int NTT, int ITEMS, bool NCHW>
 __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 {
     constexpr int MI = 2;
     constexpr int PT = WN * NI * 32; // pixel lanes per workgroup
     extern __shared__ __align__(16) unsigned char smem[];
-    const uint32_t buf_bytes = (uint32_t)p.patch_px * KCS * 2;
+    constexpr bool DEEP = NTT != 0;
+    // several groups per pass only in the kernels made for it (constants everywhere else)
+    const int t_log2 = (NTT == 4 || NTT == 8) ? p.t_log2 : 0, kcs = (NTT == 4 || NTT == 8) ? p.kcs : KCS;
+    const int KCT = KC << t_log2;                   // channels staged per pass
+    const uint32_t buf_bytes = (uint32_t)p.patch_px * kcs * 2;
 
     const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int tau = blockIdx.x % p.tiles_per_img, run = blockIdx.x / p.tiles_per_img;
@@ -359,13 +364,13 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
             // columns only; what lies outside the image is zero in both buffers from the start
             // and is never written.  ITEMS here: items per thread (1 or 2).
             const int GX = (p.Win + 7) >> 3;           // 8-pixel groups of an image row
-            const int nitems = p.IPT * p.PH * GX * (KC / 8);
+            const int nitems = (p.IPT * p.PH * GX * (KC / 8)) << t_log2;
             uint32_t e0[ITEMS], l0[ITEMS], m8[ITEMS], gq[ITEMS];
-            const int co = tid & 3;                    // channel octet of the stage
+            const int co = tid & ((4 << t_log2) - 1);  // channel octet of the stage (256 is a multiple of their number)
 #pragma unroll
             for (int q = 0; q < ITEMS; ++q) {
                 const int it = tid + 256 * q;
-                int rest = it >> 2;
+                int rest = it >> (2 + t_log2);
                 const int gx = rest % GX;
                 rest /= GX;
                 const int pr = rest % p.PH, g = rest / p.PH;
@@ -380,15 +385,15 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                 m8[q] = m;
                 gq[q] = g;
                 e0[q] = ok ? (uint32_t)((g * p.KCin + co * 8) * p.Hin + hin) * p.Win + w0 : kNoElem;
-                l0[q] = (uint32_t)(((g * p.PH + pr) * p.PWd + (w0 - win0)) * KCS + co * 8) * 2u; // (used under the mask only)
+                l0[q] = (uint32_t)(((g * p.PH + pr) * p.PWd + (w0 - win0)) * kcs + co * 8) * 2u; // (used under the mask only)
             }
             const rsrc_t rs_in = make_rsrc(p.in, (uint32_t)p.N * p.KCin * p.Hin * p.Win * 2u);
             const uint32_t plane = (uint32_t)p.Hin * p.Win;
             auto fetch = [&](int s, u32x4 (&r)[ITEMS][8]) {
                 const int u = fdiv(s, p.m_kbs), kb = kb0 + s - u * p.kbs;
                 const int n_base = (g_begin + u) * p.IPT;
-                const uint32_t sbase = (uint32_t)(n_base * p.KCin + kb * KC) * plane;
-                const int c_first = kb * KC + co * 8;   // the item's first channel
+                const uint32_t sbase = (uint32_t)(n_base * p.KCin + kb * KCT) * plane;
+                const int c_first = kb * KCT + co * 8;   // the item's first channel
                 const uint32_t lim = s < nstages ? (uint32_t)max(p.N - n_base, 0) : 0u;
 #pragma unroll
                 for (int q = 0; q < ITEMS; ++q)
@@ -409,7 +414,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                             const uint32_t lo = r[q][2 * k][px / 2], hi = r[q][2 * k + 1][px / 2];
                             v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                         }
-                        if (m8[q] & (1u << px)) *(u32x4 *)(smem + buf + l0[q] + px * (KCS * 2)) = v;
+                        if (m8[q] & (1u << px)) *(u32x4 *)(smem + buf + l0[q] + px * (kcs * 2)) = v;
                     }
             };
             u32x4 ra[ITEMS][8], rb[ITEMS][8];
@@ -430,20 +435,20 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
             }
             return;
         }
-        const int items = p.patch_px * (KC / 8);
-        const int v8 = (tid & 3) * 8;               // channel offset of this lane's items in the stage
+        const int items = (p.patch_px * (KC / 8)) << t_log2;
+        const int v8 = (tid & ((4 << t_log2) - 1)) * 8; // channel offset of this lane's items in the stage
         uint32_t eq[ITEMS], gq[ITEMS], lq[ITEMS];
 #pragma unroll
         for (int q = 0; q < ITEMS; ++q) {
             const int it = tid + 256 * q;
-            const int pp = it >> 2;
+            const int pp = it >> (2 + t_log2);
             const int g = fdiv(pp, p.m_img), rem = pp - g * (p.PH * p.PWd);
             const int pr = fdiv(rem, p.m_pwd), pc = rem - pr * p.PWd;
             const int hin = hin0 + pr, win = win0 + pc;
             const bool ok = it < items && hin >= 0 && hin < p.Hin && win >= 0 && win < p.Win;
             eq[q] = ok ? (uint32_t)((g * p.Hin + hin) * p.Win + win) * p.KCp + v8 : kNoElem;
             gq[q] = g;
-            lq[q] = it < items ? (uint32_t)(pp * KCS + v8) * 2u : 0xffffffffu;
+            lq[q] = it < items ? (uint32_t)(pp * kcs + v8) * 2u : 0xffffffffu;
         }
         const rsrc_t rs_in = make_rsrc(p.in, (uint32_t)p.N * p.Hin * p.Win * p.KCp * 2u);
         // global -> registers for stage s (dead stages load nothing but are issued all the same:
@@ -451,8 +456,8 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         auto fetch = [&](int s, u32x4 (&r)[ITEMS]) {
             const int u = fdiv(s, p.m_kbs), kb = kb0 + s - u * p.kbs;
             const int n_base = (g_begin + u) * p.IPT;
-            const uint32_t sbase = (uint32_t)n_base * p.Hin * p.Win * p.KCp + kb * KC;
-            const bool lane_ok = s < nstages && kb * KC + v8 < p.KCp;
+            const uint32_t sbase = (uint32_t)n_base * p.Hin * p.Win * p.KCp + kb * KCT;
+            const bool lane_ok = s < nstages && kb * KCT + v8 < p.KCp;
             const uint32_t lim = lane_ok ? (uint32_t)max(p.N - n_base, 0) : 0u;
 #pragma unroll
             for (int q = 0; q < ITEMS; ++q) {
@@ -508,7 +513,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
         pi[ni] = ok ? i : -1;
         pj[ni] = j;
         pg[ni] = g;
-        pbase[ni] = ok ? (uint32_t)(((g * p.PH + (i - i0) * p.is) * p.PWd + j * p.is) * KCS * 2) : 0u;
+        pbase[ni] = ok ? (uint32_t)(((g * p.PH + (i - i0) * p.is) * p.PWd + j * p.is) * kcs * 2) : 0u;
     }
 
     f32x16 acc[MI][NI];
@@ -526,11 +531,15 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     // filter fragments and LDS byte offset of the tap within the patch (with this half-wave's
     // 8 channels).
     constexpr uint32_t kFrag = 64 * 16; // bytes of one fragment of the repacked filter
+    // With T groups of 32 channels per pass, entry tt stands for (tap tt / T, group tt % T): the
+    // loops below run over these "taps" and do not know the difference.
     uint32_t wofs[9], toff[9];
+    const int ksteps = (KC / 16) << t_log2;         // 16-channel steps of a pass per tap
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        wofs[t] = (uint32_t)p.wtap[t] * kblks * mblks * kFrag;
-        toff[t] = (uint32_t)(((p.dh[t] - p.dhmin) * p.PWd + (p.dw[t] - p.dwmin)) * KCS + 8 * half) * 2u;
+    for (int tt = 0; tt < 9; ++tt) {
+        const int t = tt >> t_log2, tb = tt & ((1 << t_log2) - 1);
+        wofs[tt] = ((uint32_t)p.wtap[t] * kblks + tb * (KC / 16)) * mblks * kFrag;
+        toff[tt] = (uint32_t)(((p.dh[t] - p.dhmin) * p.PWd + (p.dw[t] - p.dwmin)) * kcs + tb * KC + 8 * half) * 2u;
     }
     // this lane's part of a fragment address; a dead wave reads nothing
     const uint32_t wlane = wave_live ? (uint32_t)(m0 >> 5) * kFrag + lane * 16u : kNoLoad;
@@ -547,7 +556,8 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     // vector cache at full MFMA rate.  A stage is 18 steps, a multiple of D, so that step q of
     // every stage uses ring slot q % D and, once the steps are unrolled, every slot is a fixed
     // register.  The uniform part of a fragment's address goes into the load's scalar offset.
-    constexpr int D = NI >= 4 ? 3 : 6, STEPS = 9 * (KC / 16); // (a step of NI = 4 is twice as long)
+    constexpr int NTTS = DEEP ? NTT : 9;            // (the ring code is compiled, never run, in the kernels without it)
+    constexpr int D = NTTS == 9 ? (NI >= 4 ? 3 : 6) : 8, STEPS = NTTS * (KC / 16); // (a step of NI = 4 is twice as long)
     static_assert(STEPS % D == 0, "ring slots must not move from stage to stage");
     u32x4 wr[DEEP ? D : 1][MI];
     uint32_t wl[9];
@@ -559,12 +569,12 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
                 wr[q][mi] = __builtin_amdgcn_raw_buffer_load_b128(
-                    rs_w, wl[q >> 1], (uint32_t)((kb0 * (KC / 16) + (q & 1)) * mblks + mi) * kFrag, 0);
+                    rs_w, wl[q >> 1], (uint32_t)((kb0 * ksteps + (q & 1)) * mblks + mi) * kFrag, 0);
     } else {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            wcur[mi] = wfrag(wofs[0], kb0 * (KC / 16), mi);
-            wnxt[mi] = wfrag(wofs[0], kb0 * (KC / 16) + 1, mi);
+            wcur[mi] = wfrag(wofs[0], kb0 * ksteps, mi);
+            wnxt[mi] = wfrag(wofs[0], kb0 * ksteps + 1, mi);
         }
     }
 
@@ -590,12 +600,12 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                 for (int ni = 0; ni < NI; ++ni) bcur[ni] = *(const u32x4 *)(smem + buf + pbase[ni] + toff[0]);
             }
             if constexpr (DEEP) {
-                const uint32_t so_cur = (uint32_t)((kb0 + kb) * (KC / 16) * mblks) * kFrag;
-                const uint32_t so_nxt = (uint32_t)((kb0 + kb_next) * (KC / 16) * mblks) * kFrag;
+                const uint32_t so_cur = (uint32_t)((kb0 + kb) * ksteps * mblks) * kFrag;
+                const uint32_t so_nxt = (uint32_t)((kb0 + kb_next) * ksteps * mblks) * kFrag;
                 // pixel operands: a ring of DB steps in registers of their own (a copy from a
                 // "next" to a "current" set lets the compiler merge the two and issue the LDS read
                 // only after the current value's last use, a fraction of a step ahead)
-                constexpr int DB = NI >= 4 ? 2 : 3;
+                constexpr int DB = (NI >= 4 || NTTS != 9) ? 2 : 3;
                 static_assert(STEPS % DB == 0, "ring slots must not move from stage to stage");
                 u32x4 bq[DB][NI];
                 auto pixels = [&](int q, int ni) { return *(const u32x4 *)(smem + buf + pbase[ni] + toff[q >> 1] + 32 * (q & 1)); };
@@ -652,7 +662,7 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                 const bool last = t + 1 >= p.ntaps;
                 const uint32_t wo_n = last ? wofs[0] : wofs[t + 1 < 9 ? t + 1 : 0];
                 const uint32_t to_n = toff[t + 1 < 9 ? t + 1 : 0];
-                const int kblk_n = (kb0 + (last ? kb_next : kb)) * (KC / 16);
+                const int kblk_n = (kb0 + (last ? kb_next : kb)) * ksteps;
 #pragma unroll
                 for (int kk = 0; kk < KC / 16; ++kk) {
 #pragma unroll
@@ -822,9 +832,9 @@ __global__ void __launch_bounds__(256) gather_finish_kernel(const float *__restr
     *((u32x2 *)out + q) = v;
 }
 
-template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS, bool NCHW> hipError_t launch_gather_items(const GatherParams &p, hipStream_t st)
+template <int NI, int WM, int WN, bool TR, int NTT, int ITEMS, bool NCHW> hipError_t launch_gather_items(const GatherParams &p, hipStream_t st)
 {
-    auto kern = conv_gather_kernel<NI, WM, WN, TR, DEEP, ITEMS, NCHW>;
+    auto kern = conv_gather_kernel<NI, WM, WN, TR, NTT, ITEMS, NCHW>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -833,7 +843,7 @@ template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS, bool NCHW> hipE
     }
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw;
     dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM, p.ksplit);
-    const size_t lds = (size_t)2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * ((NI < 2 ? NI : 2) * 64 + 16) : 0);
+    const size_t lds = (size_t)2 * p.patch_px * p.kcs * 2 + (p.wide_store ? 4 * 64 * ((NI < 2 ? NI : 2) * 64 + 16) : 0);
     hipLaunchKernelGGL(kern, grid, dim3(512), lds, st, p);
     if (p.ksplit > 1) {
         const long quads = (long)p.N * p.M * p.Hc * p.Wc / 4;
@@ -844,13 +854,13 @@ template <int NI, int WM, int WN, bool TR, bool DEEP, int ITEMS, bool NCHW> hipE
 }
 
 // (small patches: half the items, half the loads per stage and a shorter start-up)
-template <int NI, int WM, int WN, bool TR, bool DEEP> hipError_t launch_gather_shape(const GatherParams &p, hipStream_t st)
+template <int NI, int WM, int WN, bool TR, int NTT> hipError_t launch_gather_shape(const GatherParams &p, hipStream_t st)
 {
     if (p.nchw) // items of 8 x 8 elements, one or two per copy thread
-        return p.IPT * p.PH * ((p.Win + 7) / 8) * (KC / 8) <= 256 ? launch_gather_items<NI, WM, WN, TR, DEEP, 1, true>(p, st)
-                                                                   : launch_gather_items<NI, WM, WN, TR, DEEP, 2, true>(p, st);
-    return p.patch_px * (KC / 8) <= 256 * 6 ? launch_gather_items<NI, WM, WN, TR, DEEP, 6, false>(p, st)
-                                            : launch_gather_items<NI, WM, WN, TR, DEEP, kMaxItems, false>(p, st);
+        return p.IPT * p.PH * ((p.Win + 7) / 8) * (KC / 8) * p.T <= 256 ? launch_gather_items<NI, WM, WN, TR, NTT, 1, true>(p, st)
+                                                                         : launch_gather_items<NI, WM, WN, TR, NTT, 2, true>(p, st);
+    return p.patch_px * (KC / 8) * p.T <= 256 * 6 ? launch_gather_items<NI, WM, WN, TR, NTT, 6, false>(p, st)
+                                                  : launch_gather_items<NI, WM, WN, TR, NTT, kMaxItems, false>(p, st);
 }
 
 template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p, hipStream_t st)
@@ -858,8 +868,13 @@ template <int NI, int WM, int WN> hipError_t launch_gather(const GatherParams &p
     // runs of 4 pixels are contiguous and 8-byte aligned: the class grid is the whole output
     // plane and a plane is a multiple of 4 pixels
     const bool packed = p.os == 1 && p.Hc == p.Hout && p.Wc == p.Wout && (p.Hc * p.Wc) % 4 == 0;
-    if (p.ntaps == 9) return packed ? launch_gather_shape<NI, WM, WN, true, true>(p, st) : launch_gather_shape<NI, WM, WN, false, true>(p, st);
-    return packed ? launch_gather_shape<NI, WM, WN, true, false>(p, st) : launch_gather_shape<NI, WM, WN, false, false>(p, st);
+    // (the planner gives T > 1 only where taps x T is 4 or 8)
+    const int ntt = p.ntaps * p.T;
+    if (ntt == 9 && p.T == 1) return packed ? launch_gather_shape<NI, WM, WN, true, 9>(p, st) : launch_gather_shape<NI, WM, WN, false, 9>(p, st);
+    if (ntt == 8) return packed ? launch_gather_shape<NI, WM, WN, true, 8>(p, st) : launch_gather_shape<NI, WM, WN, false, 8>(p, st);
+    if (ntt == 4) return packed ? launch_gather_shape<NI, WM, WN, true, 4>(p, st) : launch_gather_shape<NI, WM, WN, false, 4>(p, st);
+    if (p.T != 1) return hipErrorInvalidValue; // (never planned)
+    return packed ? launch_gather_shape<NI, WM, WN, true, 0>(p, st) : launch_gather_shape<NI, WM, WN, false, 0>(p, st);
 }
 
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
@@ -915,6 +930,25 @@ bool shape_gather(GatherParams &p, int *variant)
             q.patch_px = q.IPT * q.PH * q.PWd;
             if (q.patch_px * (KC / 8) > 256 * kMaxItems) continue;
             if ((long)2 * q.patch_px * KCS * 2 > 110 * 1024) continue; // (leaves room for the epilogue's transpose)
+            // Few taps: several 32-channel groups per pass, which the kernel treats as further taps,
+            // so that taps x groups is 4 or 8 and the kernels with the deep operand rings apply
+            // (with one or two taps a pass is otherwise a handful of MFMAs, and the filter
+            // fragments, requested two steps ahead, arrive long after they are wanted).  As many
+            // groups as the channels, LDS and the copy threads' registers allow -- and, where the
+            // input could be read in place with one group, only as many as still allow that.
+            q.T = 1;
+            const int items_in_place = q.IPT * q.PH * ((q.Win + 7) / 8) * (KC / 8);
+            for (int t : {4, 2}) {
+                if ((q.ntaps * t != 8 && q.ntaps * t != 4) || KC * (t - 1) >= q.KCp) continue;
+                if (q.patch_px * (KC / 8) * t > 256 * kMaxItems) continue;
+                if ((long)2 * q.patch_px * (KC * t + 8) * 2 > 124 * 1024) continue; // (with the wide stores' 36 KB still inside the CU's 160 KB)
+                if (items_in_place <= 512 && items_in_place * t > 512) continue;
+                q.T = t;
+                break;
+            }
+            q.t_log2 = q.T == 4 ? 2 : q.T == 2 ? 1 : 0;
+            q.kcs = KC * q.T + 8;
+            q.nkb = (q.KCp + KC * q.T - 1) / (KC * q.T);
             q.m_img = magic(q.PH * q.PWd);
             q.ngrp = (q.N + q.IPT - 1) / q.IPT;
             const int mtiles = (q.Mp / 64 + wm - 1) / wm;
@@ -931,9 +965,12 @@ bool shape_gather(GatherParams &p, int *variant)
                 const long runs = (q.ngrp + q.gpw - 1) / q.gpw;
                 const long wgs = (long)q.tiles_per_img * runs * mtiles * ks;
                 // cycles per step as measured (vector-cache bound below NI = 4), two-step prefetch 1.35 x
-                const double step = (ni == 1 ? 150.0 : 235.0) * (q.ntaps == 9 ? 1.0 : 1.35);
-                const double t_wg = (double)q.gpw * q.kbs * 2 * q.ntaps * step + 8000.0;
-                const double l2_bytes = (double)wgs * q.gpw * q.kbs * KC * 2.0 * (q.ntaps * 64.0 * wm + q.patch_px);
+                // (without the deep rings a step waits for its filter fragments: measured 700-1000 cycles;
+                // with them on few taps, where every fragment is used once, 500-600)
+                const int ntt = q.ntaps * q.T;
+                const double step = ntt == 9 ? (ni == 1 ? 150.0 : 235.0) : (ntt == 4 || ntt == 8) ? (ni == 1 ? 500.0 : 600.0) : 800.0;
+                const double t_wg = (double)q.gpw * q.kbs * 2 * q.ntaps * q.T * step + 8000.0;
+                const double l2_bytes = (double)wgs * q.gpw * q.kbs * KC * q.T * 2.0 * (q.ntaps * 64.0 * wm + q.patch_px);
                 double cost = max((double)((wgs + 255) / 256) * t_wg, l2_bytes / 6000.0 + 8000.0);
                 cost += l2_bytes / 6000.0 * 0.01; // between equals, the one that moves less
                 if (ks > 1) cost += 6000.0 + (double)ks * q.N * q.M * ppi * 8.0 / 2500.0;
@@ -1033,7 +1070,7 @@ bool plan_dx(const Geom &g, int dtype, GatherParams &base, GatherParams (&cls)[4
 bool dx_reads_in_place(const Geom &g, const GatherParams (&cls)[4], int ncls)
 {
     bool direct = g.Q % 2 == 0 && (long)g.N * g.K * g.P * g.Q >= 8L * g.R * g.S * g.K * g.C;
-    for (int k = 0; k < ncls; ++k) direct = direct && cls[k].IPT * cls[k].PH * ((g.Q + 7) / 8) * (KC / 8) <= 512;
+    for (int k = 0; k < ncls; ++k) direct = direct && cls[k].IPT * cls[k].PH * ((g.Q + 7) / 8) * (KC / 8) * cls[k].T <= 512;
     return direct;
 }
 
@@ -1042,9 +1079,9 @@ int describe_one(const GatherParams &p, int variant, char *buf, size_t len)
     static const int shape[6][3] = {{2, 1, 4}, {2, 2, 2}, {2, 4, 1}, {1, 1, 4}, {1, 2, 2}, {1, 4, 1}}; // NI, WM, WN
     const int *v = shape[variant];
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw, mt = (p.Mp / 64 + v[1] - 1) / v[1];
-    return snprintf(buf, len, "gather tile=%dch x %dpx (NI=%d WM=%d WN=%d) taps=%d img/tile=%d patch=%dx%d units/wg=%d grid=%dx%dx%d lds=%dB",
-                    64 * v[1], 32 * v[0] * v[2], v[0], v[1], v[2], p.ntaps, p.IPT, p.PH, p.PWd, p.gpw, p.tiles_per_img * runs, mt,
-                    p.ksplit, 2 * p.patch_px * KCS * 2 + (p.wide_store ? 4 * 64 * ((v[0] < 2 ? v[0] : 2) * 64 + 16) : 0));
+    return snprintf(buf, len, "gather tile=%dch x %dpx (NI=%d WM=%d WN=%d) taps=%d ch/pass=%d img/tile=%d patch=%dx%d units/wg=%d grid=%dx%dx%d lds=%dB",
+                    64 * v[1], 32 * v[0] * v[2], v[0], v[1], v[2], p.ntaps, KC * p.T, p.IPT, p.PH, p.PWd, p.gpw, p.tiles_per_img * runs, mt,
+                    p.ksplit, 2 * p.patch_px * p.kcs * 2 + (p.wide_store ? 4 * 64 * ((v[0] < 2 ? v[0] : 2) * 64 + 16) : 0));
 }
 
 // Workspace: [channels-last input][repacked filter][float sums of shared-out channels], each
@@ -1120,7 +1157,7 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     // Where the pooled map cannot come out of the repack anyway, X is read where it lies under the
     // same conditions as dY in the data gradient (no channels-last copy, only the filter repack).
     const bool direct = g.W % 2 == 0 && (long)g.N * g.C * g.H * g.W >= 8L * g.R * g.S * g.K * g.C &&
-                        p.IPT * p.PH * ((g.W + 7) / 8) * (KC / 8) <= 512;
+                        p.IPT * p.PH * ((g.W + 7) / 8) * (KC / 8) * p.T <= 512;
     const bool fuse = fuse0; // (with `direct` the repack launch forms Z without writing the channels-last copy)
     *err = launch_repack(direct && !fuse ? nullptr : (const bf16_t *)X, direct ? nullptr : in, g.N, g.C, g.H * g.W, p.KCp,
                          (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total, p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
