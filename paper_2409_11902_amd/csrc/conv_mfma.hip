@@ -316,7 +316,8 @@ __global__ void __launch_bounds__(256) zero_fill_kernel(bf16_t *dst, long n)
 // software pipeline: the copy waves keep two stages of global loads in flight and write the patch
 // of stage s+1 into the LDS buffer the MFMA waves are not reading (one barrier per stage).
 // Filter fragments come straight from global memory (fragment order, cache resident), fetched
-// ahead by the MFMA waves themselves -- six steps with nine taps (DEEP), else two -- whose only
+// ahead by the MFMA waves themselves -- six steps with nine taps, eight where taps x channel groups of
+// a pass is 4 or 8 (NTT), else two -- whose only
 // other memory traffic is LDS reads, so their load counter never waits on the long-latency
 // patch loads.
 constexpr int kMaxItems = 12; // 16-byte patch items a copy thread moves per stage, at most (kernel parameter ITEMS: 6 or 12)
@@ -552,8 +553,8 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
     // operands (LDS) are requested one step ahead.
     static_assert(KC / 16 == 2, "the prefetch distance below is one tap");
     u32x4 wcur[MI], wnxt[MI], wnn[MI];
-    // DEEP (nine taps): a ring of D steps of fragments instead, enough to cover a miss in the
-    // vector cache at full MFMA rate.  A stage is 18 steps, a multiple of D, so that step q of
+    // DEEP (NTT = 9, 8 or 4 "taps" a pass): a ring of D steps of fragments instead, enough to cover a miss
+    // in the vector cache at full MFMA rate.  A stage is 2 * NTT steps, a multiple of D, so that step q of
     // every stage uses ring slot q % D and, once the steps are unrolled, every slot is a fixed
     // register.  The uniform part of a fragment's address goes into the load's scalar offset.
     constexpr int NTTS = DEEP ? NTT : 9;            // (the ring code is compiled, never run, in the kernels without it)
