@@ -94,6 +94,12 @@ SMALL = [
     ("1x1 s2 even grid wide", 2, 64, 128, 16, 24, 1, 1, 2, 0, 2),
     ("1x1 s2 even grid 5 img", 5, 32, 32, 8, 8, 1, 1, 2, 0, 2),
     ("1x1 s2 rows of 6", 2, 32, 64, 12, 6, 1, 1, 2, 0, 2),
+    # few taps: four 32-channel groups per pass, the last of them partly (100 -> 112 of 128 channels) or
+    # wholly (200 -> 208 of 256) beyond the tensor's channels; two groups with the four-tap class of a
+    # stride-2 data gradient
+    ("1x1 c100", 3, 100, 72, 10, 10, 1, 1, 1, 0, 2),
+    ("1x1 c200 s2", 2, 200, 64, 8, 8, 1, 1, 2, 0, 2),
+    ("3x3 s2 k112", 2, 40, 112, 12, 12, 3, 3, 2, 1, 2),
     # deep layers on tiny maps: forward and data gradient share a tile's channel blocks out over
     # several workgroups (float partial sums + a finishing pass); 160 channels = 5 blocks
     ("4x4 maps deep", 4, 256, 128, 4, 4, 3, 3, 1, 1, 2),
