@@ -26,6 +26,8 @@ struct GatherParams {
                         // LDS elements per patch pixel (32 * T + 8); a "channel block" above is 32 * T channels
     int nchw, KCin;     // the kernel reads the input in its own layout (KCin channels) instead of a channels-last copy
     int wide_store;     // the epilogue writes 16-byte runs of 8 pixels (whole planes, a multiple of 8 pixels each)
+    int decim;          // forward, 1 x 1 filter, stride 2: `in` holds only the pixels the filter reaches (every second
+                        // one of every second row), as an image of half the extent read with stride 1
     uint32_t m_wc, m_ppi, m_pwd, m_kbs, m_img; // division magics of Wc, Hc*Wc, PWd, kbs, PH*PWd
 };
 

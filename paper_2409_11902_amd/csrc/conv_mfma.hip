@@ -60,6 +60,7 @@ struct RepackParams {
                         // input over more compute units, one block each
     bf16_t *Z;          // pooled copy of `in` written on the way (2 x 2 means), or null
     int Wimg;           // image width (only with Z)
+    int decim;          // with Z: `out` takes pixel (2h, 2w) of every 2 x 2 tile only, as an image of half the extent
     const bf16_t *W;
     bf16_t *Wt;
     int O, Cw, RS, Mp, KCp, transpose;
@@ -163,7 +164,9 @@ __device__ __forceinline__ void repack_body(const RepackParams &p, const int bid
         for (int a = 0; a < 2; ++a) {
             if (a == 1 && !pool) break;
             if (!p.out) break; // only the pooled map is wanted
-            bf16_t *dst = p.out + ((long)n * p.HW + px0 + a * p.Wimg) * p.Cp + cg * 8;
+            if (p.decim && a == 1) break; // (odd rows are not kept)
+            bf16_t *dst = p.decim ? p.out + ((long)n * (p.HW / 4) + hh * (p.Wimg / 2) + wg * 4) * p.Cp + cg * 8
+                                  : p.out + ((long)n * p.HW + px0 + a * p.Wimg) * p.Cp + cg * 8;
 #pragma unroll
             for (int px = 0; px < 8; ++px) {
                 // pixel px of the 8 channels: half px%2 of dword px/2 of every row
@@ -173,7 +176,11 @@ __device__ __forceinline__ void repack_body(const RepackParams &p, const int bid
                     const uint32_t lo = r[a][2 * k][px / 2], hi = r[a][2 * k + 1][px / 2];
                     v[k] = (px & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                 }
-                if (px0 + px < p.HW) *(u32x4 *)(dst + (long)px * p.Cp) = v; // (a plane's last item may reach past it)
+                if (p.decim) {
+                    if (!(px & 1)) *(u32x4 *)(dst + (long)(px / 2) * p.Cp) = v;
+                } else if (px0 + px < p.HW) {
+                    *(u32x4 *)(dst + (long)px * p.Cp) = v; // (a plane's last item may reach past it)
+                }
             }
         }
         if (pool4) {
@@ -262,11 +269,11 @@ __global__ void __launch_bounds__(256) repack_reduce_kernel(RepackParams p, unsi
 // tail: a deferred weight-gradient slice sum to run in the same launch, or null.
 hipError_t launch_repack(const bf16_t *in, bf16_t *out, int N, int C, int HW, int Cp, const bf16_t *W, bf16_t *Wt, int O,
                          int Cw, int RS, int Mp, int KCp, int transpose, bf16_t *Z, int Wimg, hipStream_t st,
-                         const DwReduceTail *tail = nullptr)
+                         const DwReduceTail *tail = nullptr, int decim = 0)
 {
     RepackParams p{};
     p.in = in; p.out = out; p.N = N; p.C = C; p.HW = HW; p.Cp = Cp;
-    p.Z = Z; p.Wimg = Wimg;
+    p.Z = Z; p.Wimg = Wimg; p.decim = decim;
     p.fast = HW % 2 == 0; // planes start at multiples of 4 bytes: 16-byte loads need no more
     if (!in) N = 0;       // filter only
     const int cgs = Cp / 8, cgw = cgs < 8 ? cgs : 8;
@@ -1027,6 +1034,15 @@ bool plan_fwd(const Geom &g, int dtype, GatherParams &p, int *variant)
             const int t = r * g.S + s;
             p.dh[t] = r - g.ph; p.dw[t] = s - g.pw; p.wtap[t] = t;
         }
+    // A 1 x 1 filter with stride 2 reaches one pixel of every 2 x 2 tile.  Where the repack launch goes
+    // over those tiles anyway (it forms the 2 x 2 pooled map: rows a multiple of 8 pixels, an even
+    // number of them), its channels-last copy keeps just that pixel: a quarter of the bytes to write
+    // and to stage, and the GEMM sees a stride-1 layer on an image of half the extent.
+    p.decim = g.R == 1 && g.S == 1 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 && g.kh == 2 && g.kw == 2 &&
+              !g.pmax && g.H % 2 == 0 && g.W % 8 == 0;
+    if (p.decim) {
+        p.Hin = g.H / 2; p.Win = g.W / 2; p.is = 1;
+    }
     return shape_gather(p, variant);
 }
 
@@ -1107,7 +1123,8 @@ bool describe_conv_mfma(const Geom &g, int dtype, bool data_grad, char *buf, siz
     bool empty = false;
     if (!data_grad) {
         if (!plan_fwd(g, dtype, p, &variant[0])) return false;
-        describe_one(p, variant[0], buf, len);
+        const int n = describe_one(p, variant[0], buf, len);
+        if (p.decim && n > 0 && (size_t)n + 1 < len) snprintf(buf + n, len - n, "; the copy of the input keeps one pixel of every 2 x 2 tile");
         return true;
     }
     if (!plan_dx(g, dtype, p, cls, variant, &ncls, &empty)) return false;
@@ -1157,11 +1174,12 @@ bool launch_fwd_mfma(const Geom &g, int dtype, const void *X, const void *W, con
     const bool fuse0 = Z && !g.pmax && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && (g.W % 8 == 0 || g.W == 4);
     // Where the pooled map cannot come out of the repack anyway, X is read where it lies under the
     // same conditions as dY in the data gradient (no channels-last copy, only the filter repack).
-    const bool direct = g.W % 2 == 0 && (long)g.N * g.C * g.H * g.W >= 8L * g.R * g.S * g.K * g.C &&
+    const bool direct = !p.decim && g.W % 2 == 0 && (long)g.N * g.C * g.H * g.W >= 8L * g.R * g.S * g.K * g.C &&
                         p.IPT * p.PH * ((g.W + 7) / 8) * (KC / 8) * p.T <= 512;
     const bool fuse = fuse0; // (with `direct` the repack launch forms Z without writing the channels-last copy)
     *err = launch_repack(direct && !fuse ? nullptr : (const bf16_t *)X, direct ? nullptr : in, g.N, g.C, g.H * g.W, p.KCp,
-                         (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total, p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st);
+                         (const bf16_t *)W, wt, g.K, g.C, p.ntaps_total, p.Mp, p.KCp, 0, fuse ? (bf16_t *)Z : nullptr, g.W, st, nullptr,
+                         p.decim);
     *pooled = fuse;
     if (*err != hipSuccess) return true;
     p.in = direct ? (const bf16_t *)X : in;
