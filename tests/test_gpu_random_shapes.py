@@ -80,7 +80,30 @@ def _workload_like_specs(count, seed):
     return out
 
 
-SPECS = _random_specs(48, seed=20240911) + _mfma_leaning_specs(40, seed=7) + _workload_like_specs(24, seed=3)
+def _few_tap_specs(count, seed):
+    """1x1 and stride-2 layers with 96 to 320 channels on even and odd maps: launches with one, two or four
+    taps, which stage several 32-channel groups per pass (the last group often only partly real)
+    and, for a 1x1 stride-2 forward pass on rows of a multiple of 8 pixels, a decimated input copy."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 1, 3]))
+        stride = int(rng.choice([1, 2, 2])) if R == 1 else 2
+        H = int(rng.choice([4, 6, 7, 8, 12, 14, 16, 24, 28]))
+        W = H if rng.random() < 0.5 else int(rng.choice([8, 16, 24, 12, 14, 6]))
+        N = int(rng.integers(1, 12))
+        C = int(rng.choice([96, 100, 112, 128, 160, 200, 256, 320]))
+        K = int(rng.choice([32, 64, 96, 112, 128, 200, 256]))
+        k = int(rng.choice([1, 2, 2, 2, 4]))
+        if N * C * K * H * W * R * R > 1.5e9:
+            continue
+        out.append(synth.LayerSpec(f"ft{len(out)} N{N} C{C} K{K} {H}x{W} R{R} s{stride} k{k}",
+                                   N, C, K, H, W, R, R, stride, 0 if R == 1 else 1, k, synth.BF16))
+    return out
+
+
+SPECS = (_random_specs(48, seed=20240911) + _mfma_leaning_specs(40, seed=7) + _workload_like_specs(24, seed=3) +
+         _few_tap_specs(32, seed=5))
 
 
 @pytest.mark.parametrize("spec", SPECS, ids=[s.name for s in SPECS])
