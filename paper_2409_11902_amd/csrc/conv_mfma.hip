@@ -85,6 +85,28 @@ __device__ __forceinline__ void repack_body(const RepackParams &p, const int bid
         // used (at most 8 rows of 3 x 64 elements, or 4 rows of 5 x 64)
         constexpr int kRowsPerWave = 8, kMaxX = 5;
         const rsrc_t rs = make_rsrc(p.W, (uint32_t)p.O * p.Cw * p.RS * 2u);
+        // Whole blocks whose runs are multiples of 16 bytes and start on such (every row of W does
+        // when Cw * RS is a multiple of 8): 16-byte loads, at most 3 per thread, instead of up to 40
+        // loads of one element each.
+        const int segs = L >> 3;
+        if ((L & 7) == 0 && ((p.Cw * p.RS) & 7) == 0 && c0 + cols <= p.Cw) {
+            u32x4 t4[3];
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const int it = threadIdx.x + 256 * q, r = it / segs, sg = it - r * segs, o = o0 + r;
+                const bool ok = it < rows * segs && o < p.O;
+                t4[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? ((uint32_t)(o * p.Cw + c0) * p.RS) * 2u + sg * 16u : kNoLoad, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const int it = threadIdx.x + 256 * q, r = it / segs, sg = it - r * segs;
+                if (it < rows * segs) {
+                    uint32_t *d = (uint32_t *)(sm + r * Lp + sg * 8); // (Lp is even: 4-byte aligned)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) d[k] = t4[q][k];
+                }
+            }
+        } else {
         uint16_t tmp[kRowsPerWave][kMaxX];
 #pragma unroll
         for (int j = 0; j < kRowsPerWave; ++j) {
@@ -105,6 +127,7 @@ __device__ __forceinline__ void repack_body(const RepackParams &p, const int bid
                 const int x = ln + 64 * k;
                 if (r < rows && x < L) sm[r * Lp + x] = tmp[j][k];
             }
+        }
         }
         __syncthreads();
         for (int it = threadIdx.x; it < p.RS * 64; it += 256) {
