@@ -215,3 +215,12 @@ def test_data_gradient_reads_dy_in_place_where_pixels_outnumber_the_filter():
         assert "dY read in place" in B.cac_describe_plan(d, B.OP_BWD_DATA)
     d = B.make_desc(128, 512, 512, 4, 4, 3, 3, 1, 1, 1, 1, 2, 2, dtype=B.BF16)
     assert "dY read in place" not in B.cac_describe_plan(d, B.OP_BWD_DATA)
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """One GPU only: asked for more, the benchmark says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout) and r.stdout.strip() == ""
