@@ -820,19 +820,31 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
                             for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.f;
                 } else {
                     // register j of lane l: channel 8*(j/4) + 4*(l/32) + j%4, pixel l%32 of the block
+                    // Stores through a buffer descriptor over the whole output (less than 2^31 bytes on this
+                    // path): 32-bit offsets, split into the pixel's part (per block) and the channel's, and
+                    // an offset past the tensor instead of a branch for lanes that own no output.
+                    const rsrc_t rs_out = make_rsrc(p.out, (uint32_t)p.N * p.M * p.Hout * p.Wout * 2u);
+                    const uint32_t plane_out = (uint32_t)p.Hout * p.Wout;
+                    uint32_t obase[NI];
+                    bool oky[NI];
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const int n = n_base + pg[ni];
+                        const int h = pi[ni] * p.os + p.a0, w = pj[ni] * p.os + p.b0;
+                        oky[ni] = pi[ni] >= 0 && n < p.N;
+                        obase[ni] = oky[ni] ? ((uint32_t)n * p.M * plane_out + h * p.Wout + w) * 2u : 0u;
+                    }
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                         for (int j = 0; j < 16; ++j) {
                             const int m = m0 + mi * 32 + 8 * (j / 4) + 4 * half + (j % 4);
                             const float bias = (p.bias && m < p.M) ? bf16_to_f32(p.bias[m]) : 0.f;
+                            const uint32_t moff = (uint32_t)min(m, p.M) * plane_out * 2u;
 #pragma unroll
                             for (int ni = 0; ni < NI; ++ni) {
-                                const int n = n_base + pg[ni];
-                                if (m < p.M && pi[ni] >= 0 && n < p.N) {
-                                    const int h = pi[ni] * p.os + p.a0, w = pj[ni] * p.os + p.b0;
-                                    p.out[(((long)n * p.M + m) * p.Hout + h) * p.Wout + w] = f32_to_bf16(acc[mi][ni][j] + bias);
-                                }
+                                const uint32_t off = (m < p.M && oky[ni]) ? obase[ni] + moff : kNoLoad;
+                                __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16(acc[mi][ni][j] + bias), rs_out, off, 0, 0);
                                 acc[mi][ni][j] = 0.f;
                             }
                         }
