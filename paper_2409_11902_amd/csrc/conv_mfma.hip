@@ -160,13 +160,14 @@ __device__ __forceinline__ void repack_body(const RepackParams &p, const int bid
         const int pgs = pool ? p.HW / 16 : (p.HW + 7) / 8;     // items along the pixels (the last may be partial)
         const int cgs = p.Cp / 8, cgw = min(cgs, 8), cgb = (cgs + cgw - 1) / cgw;
         if ((int)(threadIdx.x >> 6) >= p.in_wpb) return;
-        const long item = ((long)bid * p.in_wpb + (threadIdx.x >> 6)) * 64 + (threadIdx.x & 63);
-        if (item >= (long)p.N * cgb * pgs * cgw) return;
-        const int cl = item % cgw;
-        long t1 = item / cgw;
-        const int pi = t1 % pgs;
-        t1 /= pgs;
-        const int cg = (int)(t1 % cgb) * cgw + cl, n = t1 / cgb;
+        // (fewer than 2^31 items: 32-bit divisions)
+        const uint32_t item = ((uint32_t)bid * p.in_wpb + (threadIdx.x >> 6)) * 64u + (threadIdx.x & 63);
+        if (item >= (uint32_t)p.N * cgb * pgs * cgw) return;
+        const int cl = item % (uint32_t)cgw;
+        uint32_t t1 = item / (uint32_t)cgw;
+        const int pi = t1 % (uint32_t)pgs;
+        t1 /= (uint32_t)pgs;
+        const int cg = (int)(t1 % (uint32_t)cgb) * cgw + cl, n = t1 / (uint32_t)cgb;
         if (cg >= cgs) return;
         // first pixel of the item's (first) row segment
         const int hh = pool ? pi / wgs : 0, wg = pool ? pi - hh * wgs : 0;
@@ -870,7 +871,7 @@ __global__ void __launch_bounds__(256) gather_finish_kernel(const float *__restr
     const f32x4 *src = (const f32x4 *)part + q;
     f32x4 sum = src[0];
     for (int k = 1; k < nsplit; ++k) sum += src[k * quads];
-    if (bias) sum += bf16_to_f32(bias[(int)((q * 4 / ppi) % M)]);
+    if (bias) sum += bf16_to_f32(bias[((uint32_t)q * 4u / (uint32_t)ppi) % (uint32_t)M]); // (fewer than 2^30 quads)
     const u32x2 v = {f32x2_to_bf16x2(sum[0], sum[1]), f32x2_to_bf16x2(sum[2], sum[3])};
     *((u32x2 *)out + q) = v;
 }
