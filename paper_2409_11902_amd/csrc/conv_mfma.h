@@ -29,6 +29,7 @@ struct GatherParams {
     int decim;          // forward, 1 x 1 filter, stride 2: `in` holds only the pixels the filter reaches (every second
                         // one of every second row), as an image of half the extent read with stride 1
     uint32_t m_wc, m_ppi, m_pwd, m_kbs, m_img; // division magics of Wc, Hc*Wc, PWd, kbs, PH*PWd
+    uint32_t m_gx, m_ph;                       // ... of the 8-pixel groups of an input row and of PH (in-place copy)
 };
 
 size_t conv_mfma_workspace(const Geom &g, int dtype, bool data_grad);

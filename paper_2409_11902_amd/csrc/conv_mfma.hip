@@ -402,10 +402,9 @@ __global__ void __launch_bounds__(512) conv_gather_kernel(GatherParams p)
 #pragma unroll
             for (int q = 0; q < ITEMS; ++q) {
                 const int it = tid + 256 * q;
-                int rest = it >> (2 + t_log2);
-                const int gx = rest % GX;
-                rest /= GX;
-                const int pr = rest % p.PH, g = rest / p.PH;
+                const int rest = it >> (2 + t_log2);
+                const int rows = fdiv(rest, p.m_gx), gx = rest - rows * GX; // (g, pr) as one index
+                const int g = fdiv(rows, p.m_ph), pr = rows - g * p.PH;
                 const int hin = hin0 + pr, w0 = gx * 8;
                 const bool ok = it < nitems && hin >= 0 && hin < p.Hin;
                 uint32_t m = 0;
@@ -994,6 +993,7 @@ bool shape_gather(GatherParams &p, int *variant)
             q.kcs = KC * q.T + 8;
             q.nkb = (q.KCp + KC * q.T - 1) / (KC * q.T);
             q.m_img = magic(q.PH * q.PWd);
+            q.m_gx = magic((q.Win + 7) / 8); q.m_ph = magic(q.PH);
             q.ngrp = (q.N + q.IPT - 1) / q.IPT;
             const int mtiles = (q.Mp / 64 + wm - 1) / wm;
             const long wgs1 = (long)q.tiles_per_img * q.ngrp * mtiles;
