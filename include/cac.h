@@ -111,8 +111,9 @@ const char *cac_last_error(void);
 /* Host only.  Output extent of the convolution: P = floor((H+2*pad_h-R)/stride_h)+1. */
 int cac_out_shape(const cac_desc *d, int32_t *P, int32_t *Q);
 
-/* Host only.  The saved record's book-keeping ("no encoding beyond the original
- * shape": compression section; byte counts as in the per-layer memory table):
+/* Host only.  The saved record's book-keeping (compression section: the record is
+ * Z plus the original shape and the tile size, nothing else; byte counts as in the
+ * per-layer memory table):
  * pooled extent and the bytes of X and of Z in the descriptor's dtype. */
 int cac_pooled_shape(const cac_desc *d, int32_t *Hp, int32_t *Wp, size_t *z_bytes, size_t *x_bytes);
 

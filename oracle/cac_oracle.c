@@ -24,9 +24,12 @@
  *   - edge mode 0 ("ceil/valid"): Hp = ceil(H/kh); a ragged last tile is averaged
  *     over the elements it really has.  Edge mode 1 ("floor/drop"): Hp =
  *     floor(H/kh), remainder rows/columns are not pooled (this is what the
- *     per-layer memory table's byte counts imply); inflation of the dropped tail
- *     repeats the last pooled cell -- PARITY UNPINNED for that tail, the paper
- *     does not define it.
+ *     per-layer memory table's byte counts imply).  The paper does not say what
+ *     dropped rows inflate to, so oracle_inflate refuses that case (returns -1)
+ *     instead of inventing a value; floor/drop with tiles that divide the map is
+ *     the same as ceil/valid;
+ *   - the cosine of the layer-sensitivity equation is undefined for a zero
+ *     gradient; oracle_cosine returns 0 there (reading: "no agreement").
  *
  * OpenMP is used only over independent outputs; every output element is still a
  * single sequential sum in the order written here.
@@ -49,7 +52,8 @@ static int64_t out_extent(int64_t in, int64_t pad, int64_t filt, int64_t stride)
 }
 
 /* Book-keeping of the saved record: pooled extents and byte counts
- * (memory-footprint table; "no encoding beyond the original shape"). */
+ * (memory-footprint table; compression section: the record holds nothing but
+ * Z, the original shape and the tile size). */
 void oracle_pooled_shape(int64_t H, int64_t W, int64_t kh, int64_t kw, int edge_mode,
                          int64_t *Hp, int64_t *Wp)
 {
@@ -132,14 +136,16 @@ void oracle_maxpool(const double *X, int64_t N, int64_t C, int64_t H, int64_t W,
     }
 }
 
-/* Decompression: inflate Z back to H x W by replicating every pooled value over
- * its tile (compression figure caption: "inflate ... back to the original
- * dimensions"). */
-void oracle_inflate(const double *Z, int64_t N, int64_t C, int64_t H, int64_t W,
+/* Decompression (compression figure, caption): Z is brought back to H x W by
+ * replicating every pooled value over its tile.  Returns 0, or -1 without
+ * writing anything when the tiles do not cover the map (floor/drop with a
+ * remainder): the paper defines no value for the uncovered pixels. */
+int oracle_inflate(const double *Z, int64_t N, int64_t C, int64_t H, int64_t W,
                     int64_t kh, int64_t kw, int edge_mode, double *Xhat)
 {
     int64_t Hp, Wp;
     oracle_pooled_shape(H, W, kh, kw, edge_mode, &Hp, &Wp);
+    if (Hp * kh < H || Wp * kw < W) return -1;
     int64_t planes = N * C;
 #pragma omp parallel for schedule(static)
     for (int64_t pl = 0; pl < planes; ++pl) {
@@ -147,14 +153,13 @@ void oracle_inflate(const double *Z, int64_t N, int64_t C, int64_t H, int64_t W,
         double *xh = Xhat + pl * H * W;
         for (int64_t h = 0; h < H; ++h) {
             int64_t i = h / kh;
-            if (i >= Hp) i = Hp - 1; /* floor/drop tail only */
             for (int64_t w = 0; w < W; ++w) {
                 int64_t j = w / kw;
-                if (j >= Wp) j = Wp - 1;
                 xh[h * W + w] = z[i * Wp + j];
             }
         }
     }
+    return 0;
 }
 
 /* Forward convolution Y = X * W + b, zero padding (compression figure). */

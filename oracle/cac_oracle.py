@@ -40,6 +40,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.oracle_cosine.restype = ctypes.c_double
+        _lib.oracle_inflate.restype = ctypes.c_int
         _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -129,8 +130,10 @@ def inflate(Z, H: int, W: int, kh: int, kw: int, edge_mode: int = EDGE_CEIL_VALI
     N, C, hp, wp = Z.shape
     assert (hp, wp) == pooled_shape(H, W, kh, kw, edge_mode)
     Xh = np.empty((N, C, H, W), dtype=np.float64)
-    _load().oracle_inflate(_d(Z), _i64(N), _i64(C), _i64(H), _i64(W), _i64(kh), _i64(kw),
-                           ctypes.c_int(edge_mode), _d(Xh))
+    rc = _load().oracle_inflate(_d(Z), _i64(N), _i64(C), _i64(H), _i64(W), _i64(kh), _i64(kw),
+                                ctypes.c_int(edge_mode), _d(Xh))
+    if rc != 0:
+        raise ValueError("inflation is undefined where floor/drop tiles leave rows or columns uncovered")
     return Xh
 
 

@@ -247,6 +247,21 @@ def test_pool_and_inflate_against_torch(k, hw):
         np.testing.assert_allclose(Zf, zf.numpy(), rtol=1e-14, atol=0)
 
 
+def test_inflate_refuses_what_the_paper_leaves_undefined():
+    """Floor/drop tiles that leave rows or columns uncovered: the paper says nothing about what
+    those pixels inflate to, so the oracle has no value for them.  Where the tiles do cover the
+    map the two edge modes are the same thing."""
+    X = _rand((1, 2, 7, 8), 25, relu=True)
+    Zf = oracle.avgpool(X, 2, 2, oracle.EDGE_FLOOR_DROP)
+    assert Zf.shape == (1, 2, 3, 4)
+    with pytest.raises(ValueError):
+        oracle.inflate(Zf, 7, 8, 2, 2, oracle.EDGE_FLOOR_DROP)
+    X = _rand((1, 2, 8, 12), 26, relu=True)
+    Zf, Zc = oracle.avgpool(X, 2, 4, oracle.EDGE_FLOOR_DROP), oracle.avgpool(X, 2, 4)
+    assert np.array_equal(Zf, Zc)
+    assert np.array_equal(oracle.inflate(Zf, 8, 12, 2, 4, oracle.EDGE_FLOOR_DROP), oracle.inflate(Zc, 8, 12, 2, 4))
+
+
 @pytest.mark.parametrize("g", GEOMS[:5])
 @pytest.mark.parametrize("k", [2, 4])
 def test_compressed_dw_against_unfold_matmul(g, k):
@@ -291,6 +306,8 @@ def test_cosine_closed_forms():
     assert oracle.cosine(a, -2 * a) == pytest.approx(-1.0, abs=1e-15)
     assert oracle.cosine(a, np.array([-4.0, 3.0, 7.0])) == pytest.approx(0.0, abs=1e-15)
     assert oracle.cosine(np.array([1.0, 0.0]), np.array([1.0, 1.0])) == pytest.approx(np.sqrt(0.5), rel=1e-15)
+    # a zero gradient has no direction: the convention taken is 0, for either argument
+    assert oracle.cosine(np.zeros(3), a) == 0.0 and oracle.cosine(a, np.zeros(3)) == 0.0
 
 
 def test_compression_lowers_cosine_but_keeps_direction():
