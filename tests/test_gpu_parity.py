@@ -14,7 +14,7 @@ import pytest
 
 import oracle
 from paper_2409_11902_amd import synth
-from util import geom, rel_l2, tile_constant_activation
+from util import check_bf16_output, geom, rel_l2, tile_constant_activation
 
 pytestmark = pytest.mark.gpu
 
@@ -47,6 +47,9 @@ def _check_step(spec, t, got, has_bias=True):
         dWr = oracle.conv_dw(g, oracle.inflate(Zr, spec.H, spec.W, spec.k, spec.k), t["dY"].astype(np.float64))
         err = rel_l2(got["dW"], dWr)
         assert err <= TIGHT, f"{spec.name} dW (tight): rel-L2 {err:.3e}"
+        # Y and dX, every element: the oracle value rounded to bfloat16, or its neighbour
+        check_bf16_output(got["Y"], want["Y"], f"{spec.name} Y")
+        check_bf16_output(got["dX"], want["dX"], f"{spec.name} dX")
     else:
         err = rel_l2(got["dW"], want["dW"])
         assert err <= 1e-5

@@ -101,3 +101,41 @@ def test_mean_tiles_that_are_not_powers_of_two(c):
     for name, w in want.items():
         e = rel_l2(got[name], w)
         assert e <= TOL[dt], f"{name}: {e:.3e}"
+
+
+# Anisotropic and 8-wide tiles on shapes the MFMA weight-gradient kernel takes (3x3 pad 1 at
+# stride 1 and 2, 1x1 stride 2; channels >= 32 with an edge block; odd W, so the last tile of a
+# row is ragged; enough images for several chunks and pixel slices).
+# N, C, K, H, W, R, stride, pad, kh, kw, dtype
+MFMA_TILE_CASES = [
+    (12, 40, 72, 16, 17, 3, 1, 1, 8, 8, synth.BF16),
+    (12, 64, 33, 16, 19, 3, 1, 1, 2, 8, synth.BF16),
+    (10, 40, 64, 24, 15, 3, 1, 1, 8, 1, synth.BF16),
+    (10, 32, 72, 14, 21, 3, 1, 1, 1, 4, synth.BF16),
+    (12, 72, 40, 12, 13, 3, 1, 1, 4, 2, synth.BF16),
+    (12, 40, 72, 16, 17, 3, 2, 1, 8, 8, synth.BF16),
+    (12, 64, 33, 16, 19, 3, 2, 1, 2, 8, synth.BF16),
+    (10, 40, 64, 24, 15, 3, 2, 1, 8, 1, synth.BF16),
+    (10, 32, 72, 14, 21, 3, 2, 1, 1, 4, synth.BF16),
+    (12, 72, 40, 12, 13, 3, 2, 1, 4, 2, synth.BF16),
+    (12, 40, 72, 16, 17, 1, 2, 0, 8, 8, synth.BF16),
+    (12, 64, 33, 16, 19, 1, 2, 0, 2, 8, synth.BF16),
+    (10, 72, 64, 24, 15, 1, 2, 0, 8, 1, synth.BF16),
+    (10, 32, 72, 14, 21, 1, 2, 0, 1, 4, synth.BF16),
+    (12, 72, 40, 12, 13, 1, 2, 0, 4, 2, synth.BF16),
+]
+
+
+@pytest.mark.parametrize("c", MFMA_TILE_CASES, ids=[" ".join(map(str, c)) for c in MFMA_TILE_CASES])
+def test_anisotropic_and_wide_tiles_on_the_mfma_weight_gradient(c):
+    N, C, K, H, W, R, stride, pad, kh, kw, dt = c
+    d = B.make_desc(N, C, K, H, W, R, R, stride, stride, pad, pad, kh, kw, dtype=B.BF16, has_bias=0)
+    plan = B.cac_describe_plan(d, B.OP_BWD_WEIGHT_COMPRESSED)
+    assert plan.startswith("dw_mfma"), plan   # the case is here for that kernel's staging branches
+    g, f, got = _run(c, B.POOL_MEAN)
+    Zo = oracle.avgpool(f["X"], kh, kw)
+    Zr = synth.round_to_bf16(Zo.astype(np.float32)).astype(np.float64)
+    assert float((np.abs(got["Z"] - Zr) > np.abs(Zr) * 2.0 ** -7).mean()) == 0.0
+    want = oracle.conv_dw(g, oracle.inflate(Zr, H, W, kh, kw), f["dY"])
+    e = rel_l2(got["dW"], want)
+    assert e <= 2e-4, f"dW (tight): {e:.3e}"

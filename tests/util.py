@@ -33,3 +33,21 @@ def tile_constant_activation(spec: synth.LayerSpec, seed: int = 0) -> np.ndarray
         for w in range(spec.W):
             full[:, :, h, w] = coarse[:, :, h // k, w // k]
     return full
+
+
+def check_bf16_output(got, want, what: str) -> None:
+    """A bfloat16 output (Y, dX) against the oracle's fp64 values.  The device sums in float and
+    rounds once, so it must land on the oracle value rounded to bfloat16 by the harness or on a
+    neighbour of it: rel-L2 <= 4e-3 over the elements given and, for every single one,
+    |got - want| <= 2^-7 |want| + 2^-7 rms(want) (one bfloat16 ulp is at most 2^-7 of the value;
+    the rms term covers sums that cancel to near zero).  One wrong pixel fails the second part."""
+    got = np.asarray(got, dtype=np.float64).ravel()
+    want = np.asarray(want, dtype=np.float64).ravel()
+    wr = synth.round_to_bf16(want.astype(np.float32)).astype(np.float64)
+    err = rel_l2(got, wr)
+    assert err <= 4e-3, f"{what}: rel-L2 against the bf16-rounded oracle {err:.3e}"
+    rms = float(np.sqrt(np.mean(wr * wr))) if wr.size else 0.0
+    bound = 2.0 ** -7 * np.abs(wr) + 2.0 ** -7 * rms
+    bad = np.abs(got - wr) > bound
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} elements off by more than a bf16 ulp, first at "
+                           f"{int(np.argmax(bad))}: got {got[np.argmax(bad)]!r} want {wr[np.argmax(bad)]!r}")
