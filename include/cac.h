@@ -147,6 +147,25 @@ int cac_compress(const cac_desc *d, const void *X, void *Z, void *stream);
 int conv_bwd_weight_compressed(const cac_desc *d, const void *Z, const void *dY, void *dW,
                                void *ws, size_t ws_bytes, void *stream);
 
+/* conv_bwd_weight_compressed for callers that cannot allocate or hand over device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without the workspace, same kernels, bit-identical dW.  The scratch the kernels
+ * need (the float partial sums of the pixel slices) lives in a buffer of
+ * CAC_NOALLOC_SCRATCH_BYTES that is part of the library itself: every GPU the library is used
+ * on holds one copy of it until the process ends.  The call allocates and frees nothing.
+ *   - A layer whose weight gradient needs more scratch than that
+ *     (cac_workspace_size(CAC_OP_BWD_WEIGHT_COMPRESSED) tells) is refused with
+ *     CAC_ERR_UNSUPPORTED before anything is launched.  (The launch plans of this version keep
+ *     the partial sums to one 64 x 64 x 9 float tile per workgroup of a 256-workgroup grid,
+ *     36 MiB, so none is.)
+ *   - The first call on a GPU looks the buffer's address up once (hipGetSymbolAddress); make
+ *     that call outside stream capture.
+ *   - All calls on one GPU share that GPU's buffer: calls that may overlap on one GPU
+ *     (different streams, several host threads) race; serialise them on one stream.
+ *   - The device current at the call must be the one Z, dY and dW live on. */
+#define CAC_NOALLOC_SCRATCH_BYTES ((size_t)40 << 20)
+int conv_bwd_weight_compressed_noalloc(const cac_desc *d, const void *Z, const void *dY, void *dW, void *stream);
+
 /* Data gradient (data-gradient formula in the same figure), independent of the
  * activation and therefore exact:
  *   dX[n,c,h,w] = sum_{o,r,s} W[o,c,r,s] * dY[n,o,p,q],  p*stride_h+r-pad_h = h, q*stride_w+s-pad_w = w

@@ -28,8 +28,9 @@ POOL_MEAN, POOL_MAX = 0, 1
 EXPORTS = (
     "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size", "cac_describe_plan",
     "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias", "cac_grad_cosine",
-    "conv_bwd_weight_and_data",
+    "conv_bwd_weight_and_data", "conv_bwd_weight_compressed_noalloc",
 )
+NOALLOC_SCRATCH_BYTES = 40 << 20
 
 
 class cac_desc(ctypes.Structure):
@@ -71,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.conv_fwd_and_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cac_compress.argtypes = [dp, vp, vp, vp]
         L.conv_bwd_weight_compressed.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.conv_bwd_weight_compressed_noalloc.argtypes = [dp, vp, vp, vp, vp]
         L.conv_bwd_data.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_weight_and_data.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_bias.argtypes = [dp, vp, vp, vp]
@@ -163,6 +165,10 @@ def cac_compress(d, X, Z, stream=None):
 def conv_bwd_weight_compressed(d, Z, dY, dW, ws=None, stream=None):
     wp, wb = _ws(ws)
     _check(lib().conv_bwd_weight_compressed(ctypes.byref(d), _ptr(Z), _ptr(dY), _ptr(dW), wp, wb, _stream(stream)))
+
+
+def conv_bwd_weight_compressed_noalloc(d, Z, dY, dW, stream=None):
+    _check(lib().conv_bwd_weight_compressed_noalloc(ctypes.byref(d), _ptr(Z), _ptr(dY), _ptr(dW), _stream(stream)))
 
 
 def conv_bwd_data(d, W, dY, dX, ws=None, stream=None):

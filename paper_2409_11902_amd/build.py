@@ -1,18 +1,24 @@
-"""Builds libcac.so (the C-ABI HIP library) in-tree for gfx950 with hipcc."""
+"""Builds libcac.so (the C-ABI HIP library) in-tree for gfx950 with hipcc.
+
+Every csrc/*.hip file is compiled to an object of its own (in parallel), then linked.
+`python -m paper_2409_11902_amd.build` compiles everything; `--incremental` recompiles only
+the files that are newer than their objects (or older than a header)."""
 from __future__ import annotations
 
 import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcac.so")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU ops
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
@@ -23,14 +29,37 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
+def _headers_mtime() -> float:
+    hs = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    return max(os.path.getmtime(h) for h in hs)
+
+
+def build_library(verbose: bool = True, extra_flags=(), incremental: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB, *sources()]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    os.makedirs(OBJ, exist_ok=True)
+    hdr_t = _headers_mtime()
+    jobs = []
+    objs = []
+    for src in sources():
+        obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+        objs.append(obj)
+        fresh = os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), hdr_t)
+        if incremental and fresh and not extra_flags:
+            continue
+        jobs.append([hipcc, *HIPCC_FLAGS, *extra_flags, "-c", "-o", obj, src])
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as ex:
+        list(ex.map(run, jobs))
+    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB
 
 
 if __name__ == "__main__":
-    build_library(extra_flags=sys.argv[1:])
+    args = sys.argv[1:]
+    inc = "--incremental" in args
+    build_library(extra_flags=[a for a in args if a != "--incremental"], incremental=inc)

@@ -5,6 +5,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.h"
 #include "conv_mfma.h"
 #include "dw_mfma.h"
@@ -133,6 +135,36 @@ static hipError_t do_compress(const Geom &g, int dtype, const void *X, void *Z, 
     return launch_compress_generic(g, dtype, X, Z, st);
 }
 
+// ---- scratch of the entry point that allocates nothing ------------------------------------
+// Device memory that belongs to the library's code object: every GPU the library runs on holds
+// its own copy, at its own address, until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels and copies get the address looked up below.
+constexpr size_t kScratchBytes = CAC_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch` (looked up once per device, with that device current).
+static int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(CAC_ERR_LAUNCH_FAILED, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CAC_ERR_UNSUPPORTED, "device ordinal %d above %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(CAC_ERR_LAUNCH_FAILED, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CAC_OK;
+}
+
 } // namespace cac
 
 using namespace cac;
@@ -246,6 +278,28 @@ int conv_bwd_weight_compressed(const cac_desc *d, const void *Z, const void *dY,
     if (rc) return rc;
     if ((rc = check_ptr(Z, "Z")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dW, "dW"))) return rc;
     if ((rc = check_ws(g, d->dtype, CAC_OP_BWD_WEIGHT_COMPRESSED, ws, ws_bytes, nullptr))) return rc;
+    DwMfmaPlan plan;
+    if (dw_mfma_plan(g, d->dtype, &plan))
+        return launched(launch_dw_mfma(plan, Z, dY, (float *)dW, ws, (hipStream_t)stream), "weight gradient (MFMA)");
+    return launched(launch_dw_generic(g, d->dtype, Z, dY, (float *)dW, (hipStream_t)stream), "weight gradient");
+}
+
+int conv_bwd_weight_compressed_noalloc(const cac_desc *d, const void *Z, const void *dY, void *dW, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(Z, "Z")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dW, "dW"))) return rc;
+    const size_t need = workspace_bytes(g, d->dtype, CAC_OP_BWD_WEIGHT_COMPRESSED);
+    if (need > kScratchBytes)
+        return fail(CAC_ERR_UNSUPPORTED,
+                    "this layer's weight gradient needs %zu bytes of scratch, the built-in buffer has %zu: "
+                    "use conv_bwd_weight_compressed with a workspace of the caller's",
+                    need, kScratchBytes);
+    void *ws = nullptr;
+    if (need && (rc = scratch_of_current_device(&ws))) return rc;
+    // (nothing in the buffer has to start as zero: every pixel slice writes the whole of its
+    // partial sums before the slice sum reads them)
     DwMfmaPlan plan;
     if (dw_mfma_plan(g, d->dtype, &plan))
         return launched(launch_dw_mfma(plan, Z, dY, (float *)dW, ws, (hipStream_t)stream), "weight gradient (MFMA)");
