@@ -15,7 +15,10 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers (HIP global memory) owned by the
- *     caller, dense, NCHW / KCRS row-major, at least 16-byte aligned.
+ *     caller, dense, NCHW / KCRS row-major, at least 16-byte aligned.  (NCHW is the
+ *     only layout: the pixel sum of the weight gradient wants pixels contiguous.)
+ *   - The weight gradient's pixel slices are always summed in a fixed order: results
+ *     are reproducible bit for bit; there is no atomic mode.
  *   - dtype CAC_F32 : X, W, b, Y, Z, dY, dX are float;  dW is float.
  *     dtype CAC_BF16: X, W, b, Y, Z, dY, dX are bfloat16 (round to nearest even
  *     on every store), arithmetic accumulates in float; dW is float.
@@ -40,7 +43,7 @@
 extern "C" {
 #endif
 
-#define CAC_VERSION 200 /* major*10000 + minor*100 + patch */
+#define CAC_VERSION 300 /* major*10000 + minor*100 + patch */
 
 typedef enum cac_status {
     CAC_OK = 0,
@@ -52,7 +55,6 @@ typedef enum cac_status {
 } cac_status;
 
 typedef enum cac_dtype { CAC_F32 = 0, CAC_BF16 = 1 } cac_dtype;
-typedef enum cac_layout { CAC_NCHW = 0, CAC_NHWC = 1 /* not implemented: CAC_ERR_UNSUPPORTED */ } cac_layout;
 
 /* How a pooling tile that sticks out over the edge is treated (the paper is
  * silent; its memory table implies FLOOR_DROP, every stated invariant needs
@@ -72,6 +74,21 @@ typedef enum cac_edge_mode { CAC_EDGE_CEIL_VALID = 0, CAC_EDGE_FLOOR_DROP = 1 } 
  * maximum needs no rounding), and the backward pass inflates Z in the same way.
  * Inputs are taken to be free of NaN. */
 typedef enum cac_pool_mode { CAC_POOL_MEAN = 0, CAC_POOL_MAX = 1 } cac_pool_mode;
+
+/* How the weight gradient is evaluated.  Both give the same real number (the weight-gradient
+ * formula of the compression figure applied to the inflated Z); they differ in the work done
+ * and in rounding.
+ *   INFLATE   : Z is expanded in LDS and multiplied with dY pixel by pixel (the fused kernel the
+ *               compression section names as its goal).                               (default)
+ *   REDUCED_K : the inflated activation is constant on a tile, so the sum over the pixels of a
+ *               tile is Z times the sum of the dY values that meet it there:
+ *                 dW[o,c,r,s] = sum_{n,i,j} Z[n,c,i,j] * S_rs[n,o,i,j],
+ *                 S_rs[n,o,i,j] = sum of dY[n,o,p,q] over the (p,q) with
+ *                                 floor((p*stride_h+r-pad_h)/kh) = i, floor((q*stride_w+s-pad_w)/kw) = j.
+ *               kh*kw times fewer multiply-adds.  S is formed in float and rounded to bfloat16
+ *               once (one more storage rounding of the same size as Z's own).  Layers this
+ *               version has no such kernel for (cac_describe_plan tells) run as INFLATE. */
+typedef enum cac_dw_algo { CAC_DW_INFLATE = 0, CAC_DW_REDUCED_K = 1 } cac_dw_algo;
 
 typedef enum cac_op {
     CAC_OP_FWD_AND_COMPRESS = 0,
@@ -98,11 +115,9 @@ typedef struct cac_desc {
                                     1, 2, 4 and 8; others run on the plain ones); 1,1 = keep X */
     int32_t edge_mode;           /* cac_edge_mode */
     int32_t dtype;               /* cac_dtype */
-    int32_t layout;              /* cac_layout */
     int32_t has_bias;            /* forward adds b[C_out] when non-zero */
-    int32_t deterministic;       /* non-zero: fixed summation order in the split
-                                    weight-gradient reduction (the only mode built) */
     int32_t pool_mode;           /* cac_pool_mode */
+    int32_t dw_algo;             /* cac_dw_algo */
 } cac_desc;
 
 int cac_version(void);
@@ -119,6 +134,11 @@ int cac_pooled_shape(const cac_desc *d, int32_t *Hp, int32_t *Wp, size_t *z_byte
 
 /* Host only.  Device scratch bytes the given cac_op needs for this descriptor. */
 int cac_workspace_size(const cac_desc *d, int op, size_t *bytes);
+
+/* Host only.  Floating-point operations (2 x multiply-adds, padding of tiles not counted) that
+ * conv_bwd_weight_compressed executes for this descriptor: 2*N*P*Q*C_out*C_in*R*S for the
+ * inflating form, the pooled count for the reduced-K form where it applies. */
+int cac_dw_executed_flops(const cac_desc *d, uint64_t *flops);
 
 /* Host only.  Writes a one-line, human-readable description of the kernel and
  * launch shape the given cac_op would use for this descriptor into buf (always

@@ -13,6 +13,7 @@ from .cac_oracle import (  # noqa: F401
     build,
     conv_dw,
     conv_dw_entries,
+    conv_dw_from_tile_sums,
     conv_dx,
     conv_dx_entries,
     conv_fwd,
@@ -24,4 +25,5 @@ from .cac_oracle import (  # noqa: F401
     out_shape,
     pooled_shape,
     saved_bytes,
+    tile_sums,
 )

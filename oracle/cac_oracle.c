@@ -249,6 +249,39 @@ void oracle_conv_dw_entries(const double *A, const double *dY,
     }
 }
 
+/* Tile sums of dY for one filter tap (r, s): the inflated activation is constant on a pooling
+ * tile, so in the weight-gradient formula of the compression figure all pixels (p, q) whose tap
+ * lands in tile (i, j) meet the same value Z[n,c,i,j]; collecting them first gives
+ *   dW[o,c,r,s] = sum_{n,i,j} Z[n,c,i,j] * T[n,o,i,j],
+ *   T[n,o,i,j]  = sum of dY[n,o,p,q] over the (p, q) with
+ *                 h = p*sh + r - ph inside [0,H), w = q*sw + s - pw inside [0,W), h/kh = i, w/kw = j.
+ * (The same real number as the formula applied to the inflated Z: a regrouping of its terms.)
+ * T [N][K][Hp][Wp], ceil/valid tiles. */
+void oracle_tile_sums(const double *dY,
+                      int64_t N, int64_t C, int64_t K, int64_t H, int64_t W,
+                      int64_t R, int64_t S, int64_t sh, int64_t sw, int64_t ph, int64_t pw,
+                      int64_t kh, int64_t kw, int64_t r, int64_t s, double *T)
+{
+    (void)C;
+    int64_t P = out_extent(H, ph, R, sh), Q = out_extent(W, pw, S, sw);
+    int64_t Hp = (H + kh - 1) / kh, Wp = (W + kw - 1) / kw;
+#pragma omp parallel for schedule(static)
+    for (int64_t pl = 0; pl < N * K; ++pl) {
+        double *t = T + pl * Hp * Wp;
+        const double *g = dY + pl * P * Q;
+        for (int64_t i = 0; i < Hp * Wp; ++i) t[i] = 0.0;
+        for (int64_t p = 0; p < P; ++p) {
+            int64_t h = p * sh + r - ph;
+            if (h < 0 || h >= H) continue;
+            for (int64_t q = 0; q < Q; ++q) {
+                int64_t w = q * sw + s - pw;
+                if (w < 0 || w >= W) continue;
+                t[(h / kh) * Wp + (w / kw)] += g[p * Q + q];
+            }
+        }
+    }
+}
+
 /* Data gradient dX = W^T * dY, written as the adjoint scatter of the forward sum
  * (data-gradient formula in the compression figure).  It never sees X or Z. */
 void oracle_conv_dx(const double *Wt, const double *dY,

@@ -166,6 +166,33 @@ def conv_dw_entries(g: ConvGeom, A, dY, flat_index) -> np.ndarray:
     return out
 
 
+def tile_sums(g: ConvGeom, dY, kh: int, kw: int, r: int, s: int) -> np.ndarray:
+    """T[n,o,i,j]: sum of the dY values whose filter tap (r, s) lands in pooling tile (i, j)."""
+    dY = _f64(dY)
+    assert dY.shape == (g.N, g.K, g.P, g.Q) and 0 <= r < g.R and 0 <= s < g.S
+    hp, wp = pooled_shape(g.H, g.W, kh, kw)
+    T = np.empty((g.N, g.K, hp, wp), dtype=np.float64)
+    _load().oracle_tile_sums(_d(dY), *g._args(), _i64(kh), _i64(kw), _i64(r), _i64(s), _d(T))
+    return T
+
+
+def conv_dw_from_tile_sums(g: ConvGeom, Z, dY, kh: int, kw: int, round_sums=None) -> np.ndarray:
+    """The weight gradient of the compressed step in its regrouped form, tap by tap:
+    dW[o,c,r,s] = sum_{n,i,j} Z[n,c,i,j] * T_rs[n,o,i,j] (a plain contraction; numpy's matmul is
+    the step).  `round_sums`: applied to every T_rs first (the harness passes its storage-type
+    rounding when it checks a kernel that keeps the sums in that type)."""
+    Z = _f64(Z)
+    dW = np.empty((g.K, g.C, g.R, g.S), dtype=np.float64)
+    zf = Z.transpose(1, 0, 2, 3).reshape(g.C, -1)
+    for r in range(g.R):
+        for s in range(g.S):
+            T = tile_sums(g, dY, kh, kw, r, s)
+            if round_sums is not None:
+                T = _f64(round_sums(T))
+            dW[:, :, r, s] = T.transpose(1, 0, 2, 3).reshape(g.K, -1) @ zf.T
+    return dW
+
+
 def conv_dx(g: ConvGeom, Wt, dY) -> np.ndarray:
     Wt, dY = _f64(Wt), _f64(dY)
     assert Wt.shape == (g.K, g.C, g.R, g.S) and dY.shape == (g.N, g.K, g.P, g.Q)

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libcac.so")
 CAC_OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_ALIGNMENT, ERR_LAUNCH_FAILED = -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-NCHW, NHWC = 0, 1
+DW_INFLATE, DW_REDUCED_K = 0, 1
 EDGE_CEIL_VALID, EDGE_FLOOR_DROP = 0, 1
 POOL_MEAN, POOL_MAX = 0, 1
 (OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS, OP_GRAD_COSINE,
@@ -27,6 +27,7 @@ POOL_MEAN, POOL_MAX = 0, 1
 
 EXPORTS = (
     "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size", "cac_describe_plan",
+    "cac_dw_executed_flops",
     "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias", "cac_grad_cosine",
     "conv_bwd_weight_and_data", "conv_bwd_weight_compressed_noalloc",
 )
@@ -37,7 +38,7 @@ class cac_desc(ctypes.Structure):
     _fields_ = [("size", ctypes.c_uint32)] + [
         (n, ctypes.c_int32) for n in (
             "N", "C_in", "C_out", "H", "W", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w",
-            "pool_kh", "pool_kw", "edge_mode", "dtype", "layout", "has_bias", "deterministic", "pool_mode")
+            "pool_kh", "pool_kw", "edge_mode", "dtype", "has_bias", "pool_mode", "dw_algo")
     ]
 
 
@@ -69,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.cac_pooled_shape.argtypes = [dp, ip, ip, szp, szp]
         L.cac_workspace_size.argtypes = [dp, ctypes.c_int, szp]
         L.cac_describe_plan.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, sz]
+        L.cac_dw_executed_flops.argtypes = [dp, ctypes.POINTER(ctypes.c_uint64)]
         L.conv_fwd_and_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cac_compress.argtypes = [dp, vp, vp, vp]
         L.conv_bwd_weight_compressed.argtypes = [dp, vp, vp, vp, vp, sz, vp]
@@ -89,10 +91,9 @@ def _check(rc: int):
 
 
 def make_desc(N, C_in, C_out, H, W, R, S, stride_h=1, stride_w=1, pad_h=0, pad_w=0, pool_kh=2, pool_kw=2,
-              edge_mode=EDGE_CEIL_VALID, dtype=BF16, layout=NCHW, has_bias=1, deterministic=1,
-              pool_mode=POOL_MEAN) -> cac_desc:
+              edge_mode=EDGE_CEIL_VALID, dtype=BF16, has_bias=1, pool_mode=POOL_MEAN, dw_algo=DW_INFLATE) -> cac_desc:
     return cac_desc(ctypes.sizeof(cac_desc), N, C_in, C_out, H, W, R, S, stride_h, stride_w, pad_h, pad_w,
-                    pool_kh, pool_kw, edge_mode, dtype, layout, has_bias, deterministic, pool_mode)
+                    pool_kh, pool_kw, edge_mode, dtype, has_bias, pool_mode, dw_algo)
 
 
 def desc_from_spec(spec: synth.LayerSpec, has_bias: int = 1, **over) -> cac_desc:
@@ -133,6 +134,12 @@ def cac_describe_plan(d: cac_desc, op: int) -> str:
     buf = ctypes.create_string_buffer(2048)
     _check(lib().cac_describe_plan(ctypes.byref(d), op, buf, len(buf)))
     return buf.value.decode()
+
+
+def dw_rk_executed_flops(d: cac_desc) -> int:
+    f = ctypes.c_uint64()
+    _check(lib().cac_dw_executed_flops(ctypes.byref(d), ctypes.byref(f)))
+    return f.value
 
 
 def _ptr(t):

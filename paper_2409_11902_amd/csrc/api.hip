@@ -40,8 +40,8 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
     if (d->pad_h < 0 || d->pad_w < 0) return fail(CAC_ERR_INVALID_ARG, "padding must be non-negative");
     if (d->pool_kh <= 0 || d->pool_kw <= 0) return fail(CAC_ERR_INVALID_ARG, "pooling tile must be positive");
     if (d->dtype != CAC_F32 && d->dtype != CAC_BF16) return fail(CAC_ERR_INVALID_ARG, "unknown dtype %d", d->dtype);
-    if (d->layout != CAC_NCHW && d->layout != CAC_NHWC)
-        return fail(CAC_ERR_INVALID_ARG, "unknown layout %d", d->layout);
+    if (d->dw_algo != CAC_DW_INFLATE && d->dw_algo != CAC_DW_REDUCED_K)
+        return fail(CAC_ERR_INVALID_ARG, "unknown dw_algo %d", d->dw_algo);
     if (d->edge_mode != CAC_EDGE_CEIL_VALID && d->edge_mode != CAC_EDGE_FLOOR_DROP)
         return fail(CAC_ERR_INVALID_ARG, "unknown edge_mode %d", d->edge_mode);
     if (d->pool_mode != CAC_POOL_MEAN && d->pool_mode != CAC_POOL_MAX)
@@ -62,13 +62,10 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
     g->Wp = floor_mode ? d->W / d->pool_kw : (d->W + d->pool_kw - 1) / d->pool_kw;
 
     if (!for_kernel) return CAC_OK;
-    if (d->layout != CAC_NCHW) return fail(CAC_ERR_UNSUPPORTED, "only the NCHW layout is implemented");
     if (floor_mode && (d->H % d->pool_kh || d->W % d->pool_kw))
         return fail(CAC_ERR_UNSUPPORTED,
                     "floor/drop edge mode with a tile that does not divide the input: inflation of the dropped "
                     "rows is undefined; use CAC_EDGE_CEIL_VALID");
-    if (!d->deterministic)
-        return fail(CAC_ERR_UNSUPPORTED, "only the deterministic weight-gradient reduction is implemented");
     long x = (long)g->N * g->C * g->H * g->W, y = (long)g->N * g->K * g->P * g->Q;
     long w = (long)g->K * g->C * g->R * g->S;
     if (x > kMaxElems || y > kMaxElems || w > kMaxElems)

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert B.cac_version() == 200
+    assert B.cac_version() == 300
 
 
 def test_desc_layout_matches_header():
@@ -92,7 +92,7 @@ def _expect(code, fn, *a):
 def test_invalid_descriptors_are_rejected():
     good = dict(N=2, C_in=4, C_out=4, H=8, W=8, R=3, S=3, pad_h=1, pad_w=1)
     for bad in (dict(N=0), dict(C_in=-1), dict(H=0), dict(R=0), dict(stride_h=0), dict(pad_w=-1),
-                dict(pool_kh=0), dict(dtype=7), dict(layout=5), dict(edge_mode=3), dict(pool_mode=2), dict(pool_mode=-1),
+                dict(pool_kh=0), dict(dtype=7), dict(dw_algo=2), dict(edge_mode=3), dict(pool_mode=2), dict(pool_mode=-1),
                 dict(R=11, pad_h=0)):
         d = B.make_desc(**{**good, **bad})
         _expect(B.ERR_INVALID_ARG, B.cac_pooled_shape, d)
@@ -105,9 +105,7 @@ def test_invalid_descriptors_are_rejected():
 
 def test_unsupported_requests():
     good = dict(N=2, C_in=4, C_out=4, H=7, W=7, R=3, S=3, pad_h=1, pad_w=1)
-    _expect(B.ERR_UNSUPPORTED, B.cac_workspace_size, B.make_desc(**good, layout=B.NHWC), B.OP_BWD_DATA)
     _expect(B.ERR_UNSUPPORTED, B.cac_workspace_size, B.make_desc(**good, edge_mode=B.EDGE_FLOOR_DROP), B.OP_COMPRESS)
-    _expect(B.ERR_UNSUPPORTED, B.cac_workspace_size, B.make_desc(**good, deterministic=0), B.OP_BWD_WEIGHT_COMPRESSED)
     # floor/drop is fine when the tile divides the input
     ok = B.make_desc(**{**good, "H": 8, "W": 8}, edge_mode=B.EDGE_FLOOR_DROP)
     assert B.cac_workspace_size(ok, B.OP_COMPRESS) >= 0

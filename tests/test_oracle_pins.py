@@ -278,6 +278,45 @@ def test_compressed_dw_against_unfold_matmul(g, k):
     np.testing.assert_allclose(mine, dw.numpy(), rtol=1e-12, atol=1e-12)
 
 
+# ---------------------------------------------------------------- regrouped (tile-sum) form
+
+@pytest.mark.parametrize("g", GEOMS)
+@pytest.mark.parametrize("k", [(1, 1), (2, 2), (4, 4), (2, 4), (3, 2)])
+def test_tile_sum_form_is_the_inflated_form(g, k):
+    """Regrouping the pixel sum by pooling tile changes nothing: Z times the tile sums of dY equals
+    the weight-gradient formula applied to the inflated Z, for every stride, padding and tile."""
+    kh, kw = k
+    X = _rand((g.N, g.C, g.H, g.W), 31, relu=True)
+    dY = _rand((g.N, g.K, g.P, g.Q), 32)
+    Z = oracle.avgpool(X, kh, kw)
+    want = oracle.conv_dw(g, oracle.inflate(Z, g.H, g.W, kh, kw), dY)
+    got = oracle.conv_dw_from_tile_sums(g, Z, dY, kh, kw)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_tile_sums_by_hand_and_by_mass():
+    """3x3, stride 1, padding 1, 2x2 tiles on a 4x4 map: tap (0,0) reads input pixel (p-1, q-1), so
+    tile (0,0) (input rows 0-1, columns 0-1) collects dY at p, q in {1,2}; tap (1,1) collects the
+    aligned pairs.  Every dY value whose tap lies inside the image is counted exactly once."""
+    g = oracle.ConvGeom(1, 1, 1, 4, 4, 3, 3, 1, 1, 1, 1)
+    dY = np.arange(16, dtype=np.float64).reshape(1, 1, 4, 4)
+    T00 = oracle.tile_sums(g, dY, 2, 2, 0, 0)[0, 0]
+    assert T00[0, 0] == dY[0, 0, 1, 1] + dY[0, 0, 1, 2] + dY[0, 0, 2, 1] + dY[0, 0, 2, 2]
+    assert T00[1, 1] == dY[0, 0, 3, 3]                   # p, q in {3, 4}: only 3 exists
+    T11 = oracle.tile_sums(g, dY, 2, 2, 1, 1)[0, 0]
+    assert T11[0, 1] == dY[0, 0, 0, 2] + dY[0, 0, 0, 3] + dY[0, 0, 1, 2] + dY[0, 0, 1, 3]
+    assert T11.sum() == dY.sum()                         # the centre tap never leaves the image
+    assert T00.sum() == dY[0, 0, 1:, 1:].sum()           # row 0 / column 0 fall into the padding
+    g2 = oracle.ConvGeom(2, 1, 3, 9, 7, 3, 3, 2, 2, 1, 1)
+    dY2 = _rand((2, 3, g2.P, g2.Q), 33)
+    for r in range(3):
+        for s in range(3):
+            T = oracle.tile_sums(g2, dY2, 2, 4, r, s)
+            rows = [p for p in range(g2.P) if 0 <= 2 * p + r - 1 < 9]
+            cols = [q for q in range(g2.Q) if 0 <= 2 * q + s - 1 < 7]
+            np.testing.assert_allclose(T.sum(axis=(2, 3)), dY2[:, :, rows][:, :, :, cols].sum(axis=(2, 3)), rtol=1e-13)
+
+
 # ---------------------------------------------------------------- sampled-entry functions
 
 @pytest.mark.parametrize("g", GEOMS[:4])
