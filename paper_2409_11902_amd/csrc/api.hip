@@ -10,6 +10,7 @@
 #include "common.h"
 #include "conv_mfma.h"
 #include "dw_mfma.h"
+#include "dw_rk.h"
 
 namespace cac {
 
@@ -58,6 +59,7 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
     g->Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
     g->kh = d->pool_kh; g->kw = d->pool_kw;
     g->pmax = d->pool_mode == CAC_POOL_MAX;
+    g->dw_algo = d->dw_algo;
     g->Hp = floor_mode ? d->H / d->pool_kh : (d->H + d->pool_kh - 1) / d->pool_kh;
     g->Wp = floor_mode ? d->W / d->pool_kw : (d->W + d->pool_kw - 1) / d->pool_kw;
 
@@ -101,6 +103,8 @@ static size_t both_dw_bytes(const Geom &g, int dtype)
 static size_t workspace_bytes(const Geom &g, int dtype, int op)
 {
     if (op == CAC_OP_BWD_WEIGHT_COMPRESSED) {
+        DwRkPlan rk;
+        if (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, dtype, &rk)) return rk.partial_bytes;
         DwMfmaPlan plan;
         if (dw_mfma_plan(g, dtype, &plan)) return plan.partial_bytes; // partial sums of the pixel slices
     }
@@ -130,6 +134,20 @@ static hipError_t do_compress(const Geom &g, int dtype, const void *X, void *Z, 
     hipError_t e = hipSuccess;
     if (launch_compress_fast(g, dtype, X, Z, st, &e)) return e;
     return launch_compress_generic(g, dtype, X, Z, st);
+}
+
+// The weight gradient with the kernel the descriptor asks for (the reduced-K form where this
+// version has one for the geometry, else the inflating MFMA kernel, else the plain one).
+static int launch_weight_gradient(const Geom &g, int dtype, const void *Z, const void *dY, float *dW, void *ws, hipStream_t st,
+                                  DwReduceTail *defer)
+{
+    if (defer) defer->blocks = 0;
+    DwRkPlan rk;
+    if (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, dtype, &rk))
+        return launched(launch_dw_rk(rk, Z, dY, dW, ws, st, defer), "weight gradient (reduced K)");
+    DwMfmaPlan plan;
+    if (dw_mfma_plan(g, dtype, &plan)) return launched(launch_dw_mfma(plan, Z, dY, dW, ws, st, defer), "weight gradient (MFMA)");
+    return launched(launch_dw_generic(g, dtype, Z, dY, dW, st), "weight gradient");
 }
 
 // ---- scratch of the entry point that allocates nothing ------------------------------------
@@ -207,6 +225,20 @@ int cac_workspace_size(const cac_desc *d, int op, size_t *bytes)
     return CAC_OK;
 }
 
+int cac_dw_executed_flops(const cac_desc *d, uint64_t *flops)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if (!flops) return fail(CAC_ERR_INVALID_ARG, "flops is NULL");
+    DwRkPlan rk;
+    if (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, d->dtype, &rk))
+        *flops = rk.executed_flops;
+    else
+        *flops = 2ull * g.N * g.P * g.Q * (uint64_t)g.K * g.C * g.R * g.S;
+    return CAC_OK;
+}
+
 int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
 {
     Geom g;
@@ -215,7 +247,15 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
     if (!buf || buf_len == 0) return fail(CAC_ERR_INVALID_ARG, "buf is NULL or empty");
     if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_WEIGHT_AND_DATA) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     DwMfmaPlan plan;
-    if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && dw_mfma_plan(g, d->dtype, &plan)) {
+    DwRkPlan rk;
+    if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, d->dtype, &rk)) {
+        const DwRkParams &p = rk.p;
+        snprintf(buf, buf_len,
+                 "dw_rk tile=32x128 unit=%dimg x %dpooled rows (Z rows %d, tile-sum rows %d, blocks %d/%d) chunk=2 units "
+                 "lds=%dB units=%d slices=%d x %d tiles grid=%u partial=%zuB",
+                 p.NBIu, p.PRp, p.UZ, p.US, p.SEGS, p.SEGS_S, p.lds_bytes, p.nunits, p.nslices, p.tiles_o * p.tiles_c, rk.grid,
+                 rk.partial_bytes);
+    } else if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && dw_mfma_plan(g, d->dtype, &plan)) {
         const DwMfmaParams &p = plan.p;
         snprintf(buf, buf_len,
                  "dw_mfma variant=%d tile=%dx%d chunk=%dimg x %drows (LR=%d/%d SEGS=%d NZ=%d XW=%d) items dy=%d z=%d "
@@ -229,7 +269,9 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
         snprintf(buf, buf_len, "streaming kernel");
     } else if (op == CAC_OP_BWD_WEIGHT_AND_DATA) {
         char dx[64];
-        const bool merged = dw_mfma_plan(g, d->dtype, &plan) && !plan.p.direct && describe_conv_mfma(g, d->dtype, true, dx, sizeof dx);
+        const bool split = (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, d->dtype, &rk)) ? !rk.p.direct
+                                                                                           : (dw_mfma_plan(g, d->dtype, &plan) && !plan.p.direct);
+        const bool merged = split && describe_conv_mfma(g, d->dtype, true, dx, sizeof dx);
         snprintf(buf, buf_len, merged ? "weight gradient, then its slice sum in the launch of the data gradient's repack, then the data gradient"
                                       : "weight gradient, then data gradient, as in the separate calls");
     } else {
@@ -275,10 +317,7 @@ int conv_bwd_weight_compressed(const cac_desc *d, const void *Z, const void *dY,
     if (rc) return rc;
     if ((rc = check_ptr(Z, "Z")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(dW, "dW"))) return rc;
     if ((rc = check_ws(g, d->dtype, CAC_OP_BWD_WEIGHT_COMPRESSED, ws, ws_bytes, nullptr))) return rc;
-    DwMfmaPlan plan;
-    if (dw_mfma_plan(g, d->dtype, &plan))
-        return launched(launch_dw_mfma(plan, Z, dY, (float *)dW, ws, (hipStream_t)stream), "weight gradient (MFMA)");
-    return launched(launch_dw_generic(g, d->dtype, Z, dY, (float *)dW, (hipStream_t)stream), "weight gradient");
+    return launch_weight_gradient(g, d->dtype, Z, dY, (float *)dW, ws, (hipStream_t)stream, nullptr);
 }
 
 int conv_bwd_weight_compressed_noalloc(const cac_desc *d, const void *Z, const void *dY, void *dW, void *stream)
@@ -297,10 +336,7 @@ int conv_bwd_weight_compressed_noalloc(const cac_desc *d, const void *Z, const v
     if (need && (rc = scratch_of_current_device(&ws))) return rc;
     // (nothing in the buffer has to start as zero: every pixel slice writes the whole of its
     // partial sums before the slice sum reads them)
-    DwMfmaPlan plan;
-    if (dw_mfma_plan(g, d->dtype, &plan))
-        return launched(launch_dw_mfma(plan, Z, dY, (float *)dW, ws, (hipStream_t)stream), "weight gradient (MFMA)");
-    return launched(launch_dw_generic(g, d->dtype, Z, dY, (float *)dW, (hipStream_t)stream), "weight gradient");
+    return launch_weight_gradient(g, d->dtype, Z, dY, (float *)dW, ws, (hipStream_t)stream, nullptr);
 }
 
 int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX, void *ws, size_t ws_bytes,
@@ -330,12 +366,7 @@ int conv_bwd_weight_and_data(const cac_desc *d, const void *Z, const void *W, co
     hipStream_t st = (hipStream_t)stream;
     void *ws_dx = ws ? (char *)ws + both_dw_bytes(g, d->dtype) : nullptr;
     DwReduceTail tail{};
-    DwMfmaPlan plan;
-    if (dw_mfma_plan(g, d->dtype, &plan))
-        rc = launched(launch_dw_mfma(plan, Z, dY, (float *)dW, ws, st, &tail), "weight gradient (MFMA)");
-    else
-        rc = launched(launch_dw_generic(g, d->dtype, Z, dY, (float *)dW, st), "weight gradient");
-    if (rc) return rc;
+    if ((rc = launch_weight_gradient(g, d->dtype, Z, dY, (float *)dW, ws, st, &tail))) return rc;
     hipError_t e = hipSuccess;
     if (!launch_dx_mfma(g, d->dtype, W, dY, dX, ws_dx, st, &e, &tail)) {
         if ((rc = launched(launch_dw_reduce(tail, st), "weight gradient (slice sum)"))) return rc;

@@ -17,6 +17,7 @@ struct Geom {
     int kh, kw;         // pooling tile
     int Hp, Wp;         // pooled extent (ceil)
     int pmax;           // non-zero: a tile is reduced to its maximum instead of its mean
+    int dw_algo;        // cac_dw_algo: how the weight gradient is evaluated
 };
 
 typedef uint16_t bf16_t; // raw bfloat16 bits
