@@ -69,8 +69,8 @@ __device__ __forceinline__ bf16x8 shifted_frag(const u32x4 &lo, const u32x4 &hi)
 constexpr int kMaxZ = 4;               // 16-byte Z items a thread moves per unit
 constexpr uint32_t kNoByte = 0x80000000u; // buffer offset of a load that must return zeros
 
-// SS: 8-column blocks per tile-sum row (1, 2 or 4)
-template <int SS>
+// SS: 8-column blocks per tile-sum row (1 or 2); PART: a unit is part of an image
+template <int SS, bool PART>
 __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
 {
     constexpr int T = 9, NTM = 256, TILE_O = 32, TILE_C = 128;
@@ -114,14 +114,27 @@ __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
         const uint32_t s_sr = slot >> p.segp2_log2, s_t = slot & ((1u << p.segp2_log2) - 1);
         const bool s_task = s_sr < (uint32_t)p.US && s_t < (uint32_t)SS;
         const uint32_t s_ni = fdiv(s_sr, p.m_pr1), s_e = s_sr - s_ni * (p.PRp + 1);
-        // dword k of a loaded row holds columns 16t-2+2k and the next one: all or nothing (Q is even)
-        uint32_t s_mask = 0; // bit k: dword k lies inside the row
+        // Dword k of a loaded row holds columns 16t-2+2k and the next one: inside the row or not as
+        // a whole (Q is even).  The dword in front of a row's first block (columns -2, -1) is not
+        // loaded at all; the others are cut with lane-constant masks where any lane needs it.
+        u32x4 s_ma, s_mb;
 #pragma unroll
-        for (int k = 0; k < 9; ++k) {
-            const int col = 16 * (int)s_t - 2 + 2 * k;
-            if (col >= 0 && col < p.Q) s_mask |= 1u << k;
+        for (int k = 0; k < 4; ++k) {
+            s_ma[k] = 16 * (int)s_t + 2 * k < p.Q ? 0xffffffffu : 0u;
+            s_mb[k] = 16 * (int)s_t + 8 + 2 * k < p.Q ? 0xffffffffu : 0u;
         }
+        const bool cut_a = p.Q < 16 * (SS - 1) + 8, cut_b = p.Q < 16 * SS; // (uniform)
         const uint32_t s_lds = tab_elems + s_o * p.o_stride + s_sr * (4 * SW) + s_t * 8;
+        // A task owns the dY row pair (2e, 2e+1) of its unit-relative tile-sum row e and takes the
+        // row above (2e-1) from the task of row e-1 -- the lane SEGP2 places below -- with a DPP
+        // move; element offset of the pair's first row relative to the unit's first image and row pair
+        const int s_rel = (((int)s_ni * p.K + o0 + (int)s_o) * p.P + 2 * (int)s_e) * p.Q + 16 * (int)s_t - 2;
+        const int s_p = 2 * (int)s_e;                     // that row, relative to the unit's first row pair
+        const int s_nmax = s_task ? p.N - (int)s_ni : 0;  // the unit's first image must lie below this
+        // Units that are part of an image: the row above the unit's first pair belongs to no task of
+        // the unit; the tasks of tile-sum row 0 load it themselves.
+        constexpr bool partial = PART;
+        const bool s_first = partial && s_task && s_e == 0;
         // ---- Z: LPCZ lanes share one input channel; item j = (Z row of the unit, block)
         const uint32_t zj = tid & ((1u << p.lpcz_log2) - 1), zc = tid >> p.lpcz_log2;
         const uint32_t z_zr = fdiv(zj, p.m_segs), z_t = zj - z_zr * p.SEGS;
@@ -136,76 +149,102 @@ __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
             const int l2 = p.Wp - (int)z_t * 8 - 2 * j;
             z_mask[j] = l2 >= 2 ? 0xffffffffu : (l2 == 1 ? 0xffffu : 0u);
         }
+        const uint32_t z_rel = (((z_ni * p.C + c0 + zc) * p.Hp + z_il) * p.Wp) + z_t * 8;
+        const uint32_t z_step = z_cpp * p.Hp * p.Wp;            // elements from one pass to the next
+        const int z_nmax = z_item ? p.N - (int)z_ni : 0, z_imax = p.Hp - (int)z_il;
         const rsrc_t rs_dy = make_rsrc(p.dY, (uint32_t)p.N * p.K * p.P * p.Q * 2u);
         const rsrc_t rs_z = make_rsrc(p.Z, (uint32_t)p.N * p.C * p.Hp * p.Wp * 2u);
 
-        struct Unit { int n0, i0; bool live; };
-        auto unit_of = [&](int u) {
-            Unit t;
-            const int ig = fdiv(u, p.m_rb), rb = u - ig * p.RB;
-            t.n0 = ig * p.NBIu;
-            t.i0 = rb * p.PRp;
-            t.live = u < u_end;
-            return t;
-        };
-        // One set of copy registers: three dY rows of 18 elements (columns 16t-2 .. 16t+15: one
-        // dword, then two aligned 16-byte pieces) and the unit's Z items.
+        // One set of copy registers: two dY rows of 18 elements (columns 16t-2 .. 16t+15: one
+        // dword, then two 16-byte pieces; row 0 is the extra row above of a partial unit) and the
+        // unit's Z items.
         struct Set {
             uint32_t h[3];
             u32x4 a[3], b[3];
             u32x4 z[kMaxZ];
             uint32_t zx[kMaxZ];
+            uint32_t zsh; // bit i: item i starts on an odd element
         };
+        // the 9th element of an item that starts on an odd element is only needed when the row goes on
+        const bool z_tail = z_odd && p.Wp > 8;            // (uniform)
         // ---- global -> registers for one unit; every load is issued on every path (a lane or a
-        // unit without work loads from beyond the tensors and gets zeros)
+        // unit without work loads from beyond the tensors and gets zeros).  What depends on the
+        // unit is uniform: its first image n0 and first pooled row i0.
         auto fetch = [&](int u, Set &s) {
-            const Unit t = unit_of(u);
-            const int n = t.n0 + (int)s_ni;
-            const int pr = 2 * (t.i0 + (int)s_e) - 1; // first of the three dY rows
-            const bool ok = t.live && s_task && n < p.N;
-            const int e0 = ((n * p.K + o0 + (int)s_o) * p.P + pr) * p.Q + 16 * (int)s_t - 2;
+            const int ig = fdiv(u, p.m_rb), rb = u - ig * p.RB;
+            const int n0 = u < u_end ? ig * p.NBIu : p.N, i0 = rb * p.PRp; // (a unit past the end: no image is valid)
+            const int ubase = (n0 * p.K * p.P + 2 * i0) * p.Q;              // (uniform)
+            const bool n_ok = n0 < s_nmax;
+            const int e0 = ubase + s_rel;
 #pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                const bool row_ok = ok && pr + r >= 0 && pr + r < p.P;
-                const uint32_t off = row_ok ? (uint32_t)(e0 + r * p.Q) * 2u : kNoByte;
-                // (the single dword in front: at the very first row of the tensor its offset is
-                // "negative", i.e. far beyond the tensor, and it reads as zero, which column -1 is)
-                s.h[r] = __builtin_amdgcn_raw_buffer_load_b32(rs_dy, off, 0, 0);
+            for (int r = 1; r < 3; ++r) {
+                const bool row_ok = n_ok && (uint32_t)(2 * i0 + s_p + r - 1) < (uint32_t)p.P;
+                const uint32_t off = row_ok ? (uint32_t)(e0 + (r - 1) * p.Q) * 2u : kNoByte;
+                // (the dword in front of a row's first block would be columns -2, -1: never loaded)
+                if constexpr (SS > 1) s.h[r] = __builtin_amdgcn_raw_buffer_load_b32(rs_dy, s_t ? off : kNoByte, 0, 0);
                 s.a[r] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, off + 4u, 0, 0);
                 s.b[r] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, off + 20u, 0, 0);
             }
-            const int zn = t.n0 + (int)z_ni, zi = t.i0 + (int)z_il;
-            const bool zok = t.live && z_item && zn < p.N && zi < p.Hp;
-            const uint32_t ez = (uint32_t)(((zn * p.C + c0 + (int)zc) * p.Hp + zi) * p.Wp) + z_t * 8;
-            const uint32_t zstep = z_cpp * p.Hp * p.Wp;
+            if constexpr (partial) {
+                const bool row_ok = n_ok && s_first && i0 > 0;
+                const uint32_t off = row_ok ? (uint32_t)(e0 - p.Q) * 2u : kNoByte;
+                if constexpr (SS > 1) s.h[0] = __builtin_amdgcn_raw_buffer_load_b32(rs_dy, s_t ? off : kNoByte, 0, 0);
+                s.a[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, off + 4u, 0, 0);
+                s.b[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, off + 20u, 0, 0);
+            }
+            const bool zok = n0 < z_nmax && i0 < z_imax;
+            const uint32_t ez = (uint32_t)((n0 * p.C * p.Hp + i0) * p.Wp) + z_rel;
+            s.zsh = 0;
 #pragma unroll
             for (int i = 0; i < kMaxZ; ++i) {
-                const uint32_t e = ez + i * zstep;
+                const uint32_t e = ez + i * z_step;
                 const uint32_t off = (zok && i < p.z_passes) ? (e & ~1u) * 2u : kNoByte;
                 s.z[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_z, off, 0, 0);
-                s.zx[i] = __builtin_amdgcn_raw_buffer_load_b32(rs_z, off + 16u, 0, 0);
+                if (z_tail) s.zx[i] = __builtin_amdgcn_raw_buffer_load_b32(rs_z, off + 16u, 0, 0);
+                s.zsh |= (e & 1u) << i;
             }
         };
         // ---- registers -> LDS (unit `half` of the buffer at element offset `base`)
-        auto stage = [&](int u, int half, uint32_t base, const Set &s) {
-            // tile sums.  f[r][m]: element m of row r as a float (m = 1..17 are used)
-            float ra[18], rb[18]; // E pair sums (rows 1+2) and O pair sums (rows 0+1), per column
+        auto stage = [&](int half, uint32_t base, const Set &s) {
+            // tile sums.  Element m of a row (column 16t-2+m) as a float; m = 1..17 are used.
+            // f1, f2: the task's own rows (2e, 2e+1).  The row above (2e-1) is the lower row of the
+            // task SEGP2 lanes below: it comes in as the DPP operand of the add itself (zero where
+            // that lane lies outside the 16-lane DPP row); the first tasks of a partial unit have
+            // loaded it instead.
+            float ra[18], rb[18]; // E pair sums (rows 2e, 2e+1) and O pair sums (rows 2e-1, 2e), per column
+            auto above = [&](float lower) {
+                const int v = __builtin_bit_cast(int, lower);
+                return __builtin_bit_cast(float, SS > 1 ? __builtin_amdgcn_mov_dpp(v, 0x112, 0xf, 0xf, true)
+                                                        : __builtin_amdgcn_mov_dpp(v, 0x111, 0xf, 0xf, true));
+            };
 #pragma unroll
-            for (int k = 0; k < 9; ++k) {
+            for (int k = SS > 1 ? 0 : 1; k < 9; ++k) {
                 uint32_t w[3];
 #pragma unroll
-                for (int r = 0; r < 3; ++r) {
-                    const uint32_t d = k == 0 ? s.h[r] : k < 5 ? s.a[r][k - 1] : s.b[r][k - 5];
-                    w[r] = (s_mask >> k) & 1u ? d : 0u;
+                for (int r = 1; r < 3; ++r) {
+                    if (k == 0)
+                        w[r] = s.h[r];
+                    else if (k < 5)
+                        w[r] = cut_a ? s.a[r][k - 1] & s_ma[k - 1] : s.a[r][k - 1];
+                    else
+                        w[r] = cut_b ? s.b[r][k - 5] & s_mb[k - 5] : s.b[r][k - 5];
                 }
-                const float l0 = __uint_as_float(w[0] << 16), l1 = __uint_as_float(w[1] << 16), l2 = __uint_as_float(w[2] << 16);
-                const float h0 = __uint_as_float(w[0] & 0xffff0000u), h1 = __uint_as_float(w[1] & 0xffff0000u),
-                            h2 = __uint_as_float(w[2] & 0xffff0000u);
-                rb[2 * k] = l0 + l1;
+                const float h1 = __uint_as_float(w[1] & 0xffff0000u), h2 = __uint_as_float(w[2] & 0xffff0000u);
+                const float l1 = __uint_as_float(w[1] << 16), l2 = __uint_as_float(w[2] << 16);
+                float h0 = above(h2), l0 = above(l2);
+                if constexpr (partial) {
+                    const uint32_t x = k == 0 ? s.h[0] : k < 5 ? s.a[0][k - 1] & s_ma[k - 1] : s.b[0][k - 5] & s_mb[k - 5];
+                    h0 = s_first ? __uint_as_float(x & 0xffff0000u) : h0;
+                    l0 = s_first ? __uint_as_float(x << 16) : l0;
+                }
                 rb[2 * k + 1] = h0 + h1;
-                ra[2 * k] = l1 + l2;
                 ra[2 * k + 1] = h1 + h2;
+                if (k > 0) { // (element 0 is not used)
+                    rb[2 * k] = l0 + l1;
+                    ra[2 * k] = l1 + l2;
+                }
             }
+            if constexpr (SS == 1) ra[1] = rb[1] = 0.f; // (column -1)
             if (s_task) {
                 bf16_t *d = sW + base + s_lds + half * (p.US * 4 * SW);
                 u32x4 m0, m1, m2, m3;
@@ -224,21 +263,17 @@ __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
             }
             // Z: one element down after an odd start (rows of odd length), cut at the row's end
             if (z_item) {
-                const Unit t = unit_of(u);
-                const int zn = t.n0 + (int)z_ni, zi = t.i0 + (int)z_il;
-                const uint32_t ez = (uint32_t)(((zn * p.C + c0 + (int)zc) * p.Hp + zi) * p.Wp) + z_t * 8;
-                const uint32_t zstep = z_cpp * p.Hp * p.Wp;
                 bf16_t *zd = sW + base + z_lds + half * (p.UZ * p.ZW);
 #pragma unroll
                 for (int i = 0; i < kMaxZ; ++i) {
                     if (i < p.z_passes) {
                         u32x4 x = s.z[i];
                         if (z_odd) {
-                            const uint32_t sh = ((ez + i * zstep) & 1u) * 16u;
+                            const uint32_t sh = ((s.zsh >> i) & 1u) * 16u;
                             x[0] = __builtin_amdgcn_alignbit(s.z[i][1], s.z[i][0], sh);
                             x[1] = __builtin_amdgcn_alignbit(s.z[i][2], s.z[i][1], sh);
                             x[2] = __builtin_amdgcn_alignbit(s.z[i][3], s.z[i][2], sh);
-                            x[3] = __builtin_amdgcn_alignbit(s.zx[i], s.z[i][3], sh);
+                            x[3] = __builtin_amdgcn_alignbit(z_tail ? s.zx[i] : 0u, s.z[i][3], sh);
                         }
                         *(u32x4 *)(zd + i * z_cpp * p.c_stride) = x & z_mask;
                     }
@@ -248,6 +283,15 @@ __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
         // ---- row table of the chunk whose first unit is u: entry rho = {Z row offset, tile-sum
         // row offset} in bytes from the lane's channel base; rows that do not exist point at the
         // all-zero Z row
+        struct Unit { int n0, i0; bool live; };
+        auto unit_of = [&](int u) {
+            Unit t;
+            const int ig = fdiv(u, p.m_rb), rb = u - ig * p.RB;
+            t.n0 = ig * p.NBIu;
+            t.i0 = rb * p.PRp;
+            t.live = u < u_end;
+            return t;
+        };
         auto stage_table = [&](int u, uint32_t base) {
             if (cw == 0 && tid < p.LRZpad) {
                 const uint32_t rho = tid;
@@ -267,9 +311,9 @@ __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
         zero_fill();
         __syncthreads();
         stage_table(u_begin, base0);
-        stage(u_begin, 0, base0, A);
+        stage(0, base0, A);
         fetch(u_begin + 2, A);
-        stage(u_begin + 1, 1, base0, B);
+        stage(1, base0, B);
         fetch(u_begin + 3, B);
         __syncthreads(); // buffer 0 holds the first chunk
         for (int ck = 0; ck < nck; ck += 2) {
@@ -277,18 +321,18 @@ __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
             // end is staged all the same (zeros into a buffer nobody reads any more).
             const int u1 = u_begin + 2 * (ck + 1);
             stage_table(u1, base1);
-            stage(u1, 0, base1, A);
+            stage(0, base1, A);
             fetch(u1 + 2, A);
-            stage(u1 + 1, 1, base1, B);
+            stage(1, base1, B);
             fetch(u1 + 3, B);
             __syncthreads();
             if (ck + 1 >= nck) break;
             // MFMA waves are on buffer 1 (chunk ck+1); the sets hold chunk ck+2
             const int u2 = u1 + 2;
             stage_table(u2, base0);
-            stage(u2, 0, base0, A);
+            stage(0, base0, A);
             fetch(u2 + 2, A);
-            stage(u2 + 1, 1, base0, B);
+            stage(1, base0, B);
             fetch(u2 + 3, B);
             __syncthreads();
         }
@@ -448,9 +492,9 @@ __global__ void __launch_bounds__(512) dw_rk_kernel(DwRkParams p)
 
 uint32_t magic_of(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
 
-template <int SS> hipError_t launch_ss(const DwRkParams &p, dim3 grid, hipStream_t st)
+template <int SS, bool PART> hipError_t launch_ss(const DwRkParams &p, dim3 grid, hipStream_t st)
 {
-    auto kern = dw_rk_kernel<SS>;
+    auto kern = dw_rk_kernel<SS, PART>;
     static bool attr_set = false; // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -542,7 +586,9 @@ hipError_t launch_dw_rk(const DwRkPlan &plan, const void *Z, const void *dY, flo
     p.dY = (const bf16_t *)dY;
     p.out = p.direct ? dW : (float *)ws;
     if (defer) defer->blocks = 0;
-    hipError_t e = p.SEGS_S == 1 ? launch_ss<1>(p, dim3(plan.grid), st) : launch_ss<2>(p, dim3(plan.grid), st);
+    const bool part = p.PRp < p.Hp;
+    hipError_t e = p.SEGS_S == 1 ? (part ? launch_ss<1, true>(p, dim3(plan.grid), st) : launch_ss<1, false>(p, dim3(plan.grid), st))
+                                 : (part ? launch_ss<2, true>(p, dim3(plan.grid), st) : launch_ss<2, false>(p, dim3(plan.grid), st));
     if (e != hipSuccess || p.direct) return e;
     const DwReduceTail t = make_reduce_tail((const float *)ws, dW, (long)p.K * p.C * 9, p.nslices);
     if (defer) {
