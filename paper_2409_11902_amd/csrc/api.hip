@@ -11,6 +11,7 @@
 #include "conv_mfma.h"
 #include "dw_mfma.h"
 #include "dw_rk.h"
+#include "dw_tiled.h"
 
 namespace cac {
 
@@ -107,6 +108,8 @@ static size_t workspace_bytes(const Geom &g, int dtype, int op)
         if (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, dtype, &rk)) return rk.partial_bytes;
         DwMfmaPlan plan;
         if (dw_mfma_plan(g, dtype, &plan)) return plan.partial_bytes; // partial sums of the pixel slices
+        DwTiledPlan tl;
+        if (dw_tiled_plan(g, dtype, &tl)) return tl.partial_bytes;
     }
     // channels-last copy of the input and the repacked filter
     if (op == CAC_OP_FWD_AND_COMPRESS) return conv_mfma_workspace(g, dtype, false);
@@ -147,6 +150,8 @@ static int launch_weight_gradient(const Geom &g, int dtype, const void *Z, const
         return launched(launch_dw_rk(rk, Z, dY, dW, ws, st, defer), "weight gradient (reduced K)");
     DwMfmaPlan plan;
     if (dw_mfma_plan(g, dtype, &plan)) return launched(launch_dw_mfma(plan, Z, dY, dW, ws, st, defer), "weight gradient (MFMA)");
+    DwTiledPlan tl;
+    if (dw_tiled_plan(g, dtype, &tl)) return launched(launch_dw_tiled(tl, dtype, Z, dY, dW, ws, st, defer), "weight gradient (tiled)");
     return launched(launch_dw_generic(g, dtype, Z, dY, dW, st), "weight gradient");
 }
 
@@ -263,6 +268,10 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
                  plan.variant, p.tile_o, p.tile_c, p.NBI, p.PR, p.LR, p.LRpad, p.SEGS, p.NZ, p.XW, p.rowitems, p.citems, p.dy_passes,
                  p.z_passes, p.lds_bytes, p.nchunks, p.nslices, p.tiles_o * p.tiles_c, plan.grid,
                  plan.partial_bytes, p.dy_direct ? " dY straight into LDS" : "");
+    } else if (DwTiledPlan tl; op == CAC_OP_BWD_WEIGHT_COMPRESSED && dw_tiled_plan(g, d->dtype, &tl)) {
+        snprintf(buf, buf_len, "dw_tiled tile=16x16 unit=%d rows (LDS rows %d x %d floats) lds=%dB units=%d slices=%d x %d tiles grid=%u partial=%zuB",
+                 tl.p.PR, tl.p.XR, tl.p.XW, tl.p.lds_bytes, tl.p.nunits, tl.p.nslices, tl.p.tiles_o * tl.p.tiles_c, tl.grid,
+                 tl.partial_bytes);
     } else if ((op == CAC_OP_FWD_AND_COMPRESS || op == CAC_OP_BWD_DATA) &&
                describe_conv_mfma(g, d->dtype, op == CAC_OP_BWD_DATA, buf, buf_len)) {
     } else if (op == CAC_OP_COMPRESS || op == CAC_OP_GRAD_COSINE) {
