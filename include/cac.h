@@ -31,6 +31,11 @@
  *   - Return value: CAC_OK (0) or a negative cac_status.  Validation happens
  *     before anything is launched, so a failing call has touched no buffer.
  *     cac_last_error() gives a thread-local message for the last failing call.
+ *   - The first launch of a kernel variant in a process sets that kernel's attributes (once,
+ *     thread-safe).  Under HIP stream capture, run the same calls once eagerly before
+ *     capturing them.
+ *   - Extents: N, C_in, C_out, H, W <= 2^24; filter, stride, padding, pooling tile <= 2^15;
+ *     every tensor below 2^31 elements (CAC_ERR_UNSUPPORTED otherwise).
  *   - No C++ exception crosses this boundary.
  */
 #ifndef CAC_H

@@ -28,6 +28,13 @@ static int fail(int code, const char *fmt, ...)
 
 static const long kMaxElems = (1L << 31) - 1; // every tensor is indexed with int-sized extents
 
+// a * b * c * e without wrapping, and at most `limit`
+static bool product_fits(long a, long b, long c, long e, long limit)
+{
+    long r;
+    return !__builtin_mul_overflow(a, b, &r) && !__builtin_mul_overflow(r, c, &r) && !__builtin_mul_overflow(r, e, &r) && r <= limit;
+}
+
 // Validates the descriptor and fills the kernel geometry.  `for_kernel`: also
 // reject what only the shape queries accept.
 static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
@@ -48,6 +55,13 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
         return fail(CAC_ERR_INVALID_ARG, "unknown edge_mode %d", d->edge_mode);
     if (d->pool_mode != CAC_POOL_MEAN && d->pool_mode != CAC_POOL_MAX)
         return fail(CAC_ERR_INVALID_ARG, "unknown pool_mode %d", d->pool_mode);
+    // bounds that keep every derived extent inside int arithmetic
+    const int kMaxExtent = 1 << 24, kMaxSmall = 1 << 15;
+    if (d->N > kMaxExtent || d->C_in > kMaxExtent || d->C_out > kMaxExtent || d->H > kMaxExtent || d->W > kMaxExtent)
+        return fail(CAC_ERR_UNSUPPORTED, "an extent above 2^24");
+    if (d->R > kMaxSmall || d->S > kMaxSmall || d->stride_h > kMaxSmall || d->stride_w > kMaxSmall || d->pad_h > kMaxSmall ||
+        d->pad_w > kMaxSmall || d->pool_kh > kMaxSmall || d->pool_kw > kMaxSmall)
+        return fail(CAC_ERR_UNSUPPORTED, "filter, stride, padding or pooling tile above 2^15");
     if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S)
         return fail(CAC_ERR_INVALID_ARG, "filter larger than the padded input");
     bool floor_mode = d->edge_mode == CAC_EDGE_FLOOR_DROP;
@@ -69,9 +83,8 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
         return fail(CAC_ERR_UNSUPPORTED,
                     "floor/drop edge mode with a tile that does not divide the input: inflation of the dropped "
                     "rows is undefined; use CAC_EDGE_CEIL_VALID");
-    long x = (long)g->N * g->C * g->H * g->W, y = (long)g->N * g->K * g->P * g->Q;
-    long w = (long)g->K * g->C * g->R * g->S;
-    if (x > kMaxElems || y > kMaxElems || w > kMaxElems)
+    if (!product_fits(g->N, g->C, g->H, g->W, kMaxElems) || !product_fits(g->N, g->K, g->P, g->Q, kMaxElems) ||
+        !product_fits(g->K, g->C, g->R, g->S, kMaxElems))
         return fail(CAC_ERR_UNSUPPORTED, "a tensor has more than 2^31-1 elements");
     if (g->N > 65535) return fail(CAC_ERR_UNSUPPORTED, "N above 65535");
     return CAC_OK;
@@ -212,6 +225,8 @@ int cac_pooled_shape(const cac_desc *d, int32_t *Hp, int32_t *Wp, size_t *z_byte
     int rc = make_geom(d, &g, false);
     if (rc) return rc;
     size_t eb = d->dtype == CAC_F32 ? 4 : 2;
+    if (!product_fits(g.N, g.C, g.H, g.W, (1L << 60)))
+        return fail(CAC_ERR_UNSUPPORTED, "the byte count of X does not fit 64 bits");
     if (Hp) *Hp = g.Hp;
     if (Wp) *Wp = g.Wp;
     if (z_bytes) *z_bytes = (size_t)g.N * g.C * g.Hp * g.Wp * eb;

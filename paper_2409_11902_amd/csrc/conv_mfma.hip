@@ -21,6 +21,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "common.h"
 #include "conv_mfma.h"
 #include "dw_reduce.h"
@@ -878,12 +880,11 @@ __global__ void __launch_bounds__(256) gather_finish_kernel(const float *__restr
 template <int NI, int WM, int WN, bool TR, int NTT, int ITEMS, bool NCHW> hipError_t launch_gather_items(const GatherParams &p, hipStream_t st)
 {
     auto kern = conv_gather_kernel<NI, WM, WN, TR, NTT, ITEMS, NCHW>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // (per instantiation; once per process, whichever host thread comes first)
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&] { attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); });
+    if (attr_err != hipSuccess) return attr_err;
     const int runs = (p.ngrp + p.gpw - 1) / p.gpw;
     dim3 grid(p.tiles_per_img * runs, (p.Mp / 64 + WM - 1) / WM, p.ksplit);
     const size_t lds = (size_t)2 * p.patch_px * p.kcs * 2 + (p.wide_store ? 4 * 64 * ((NI < 2 ? NI : 2) * 64 + 16) : 0);

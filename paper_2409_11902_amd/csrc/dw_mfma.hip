@@ -35,6 +35,8 @@
 // expanded horizontally when written to LDS, expanded vertically by mapping an
 // input row h to the slot of Z row h/kh.
 
+#include <mutex>
+
 #include "common.h"
 #include "dw_mfma.h"
 #include "dw_reduce.h"
@@ -778,12 +780,11 @@ template <int R, int S, int SG, int PAD, int MI, int NI, int WM, int WN, int KS,
 hipError_t launch_fixed(const DwMfmaParams &p, dim3 grid, hipStream_t st)
 {
     auto kern = dw_mfma_kernel<R, S, SG, PAD, MI, NI, WM, WN, KS, SC, DYL>;
-    static bool attr_set = false; // per instantiation
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // (per instantiation; once per process, whichever host thread comes first)
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&] { attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); });
+    if (attr_err != hipSuccess) return attr_err;
     hipLaunchKernelGGL(kern, grid, dim3(128 * WM * WN * KS), p.lds_bytes, st, p);
     return hipGetLastError();
 }

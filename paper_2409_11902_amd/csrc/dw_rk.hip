@@ -31,6 +31,8 @@
 //                                                  2 = O rows, E cols; 3 = O rows, O cols
 //   sZ    [128 c][LRZpad rows + zero row][ZW]
 // A unit is what one set of copy registers holds (NBIu images x PRp pooled rows).
+#include <mutex>
+
 #include "common.h"
 #include "dw_rk.h"
 
@@ -495,12 +497,11 @@ uint32_t magic_of(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 <<
 template <int SS, bool PART> hipError_t launch_ss(const DwRkParams &p, dim3 grid, hipStream_t st)
 {
     auto kern = dw_rk_kernel<SS, PART>;
-    static bool attr_set = false; // per instantiation
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // (per instantiation; once per process, whichever host thread comes first)
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&] { attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); });
+    if (attr_err != hipSuccess) return attr_err;
     hipLaunchKernelGGL(kern, grid, dim3(512), p.lds_bytes, st, p);
     return hipGetLastError();
 }
