@@ -209,6 +209,33 @@ int conv_bwd_data(const cac_desc *d, const void *W, const void *dY, void *dX,
 int conv_bwd_weight_and_data(const cac_desc *d, const void *Z, const void *W, const void *dY, void *dW,
                              void *dX, void *ws, size_t ws_bytes, void *stream);
 
+/* Compression at the producer of the activation (conclusion: the pooled map is to come from the
+ * operation that makes the activation, and batch normalisation's saved activation is to be
+ * compressed as well).  `d` describes the convolution that CONSUMES the activation: its input
+ * extent N x C_in x H x W, pooling tile, edge and pooling mode, dtype.  From one read of
+ *   Y      [N][C_in][H][W]   the input of the normalisation that precedes that convolution
+ * the call writes
+ *   X_next [N][C_in][H][W]   = relu(scale[c] * Y + shift[c]), the convolution's input
+ *   Z_next [N][C_in][Hp][Wp] = pooling of X_next as stored: the convolution's saved record,
+ *                              bit for bit what cac_compress(X_next) gives
+ *   Z_in   [N][C_in][Hp][Wp] = pooling of Y: the normalisation's own saved record (NULL: not kept)
+ * scale, shift: float [C_in] on the device (batch normalisation in training mode:
+ * scale = gamma * invstd, shift = beta - mean * scale; the statistics are the caller's).
+ * X_next must not alias Y. */
+int cac_bn_relu_fwd_compress(const cac_desc *d, const void *Y, const float *scale, const float *shift, void *X_next, void *Z_next,
+                             void *Z_in, void *stream);
+
+/* Batch normalisation's backward pass from its compressed saved input (same passage: a reading,
+ * the paper gives no formulas for it).  With x~ = Z_in inflated (every pooled value repeated over
+ * its tile), xhat~ = (x~ - mean[c]) * invstd[c], M = N*H*W:
+ *   dbeta[c]  = sum dY            dgamma[c] = sum dY * xhat~
+ *   dX        = gamma[c] * invstd[c] * (dY - dbeta[c] / M - xhat~ * dgamma[c] / M)
+ * i.e. the exact formulas with the saved activation replaced by its inflated record; dbeta is
+ * exact.  mean, invstd, gamma: float [C_in], read; dgamma, dbeta: float [C_in], written; dX
+ * [N][C_in][H][W] in the tensors' type, written.  Sums are taken in a fixed order. */
+int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, const float *mean, const float *invstd,
+                          const float *gamma, float *dgamma, float *dbeta, void *dX, void *stream);
+
 /* Bias gradient (bias-gradient formula in the same figure): db[o] = sum_{n,p,q} dY.
  * db [C_out] float is overwritten. */
 int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream);

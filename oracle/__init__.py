@@ -10,6 +10,8 @@ from .cac_oracle import (  # noqa: F401
     ConvGeom,
     avgpool,
     bias_grad,
+    bn_bwd,
+    bn_relu,
     build,
     conv_dw,
     conv_dw_entries,

@@ -224,6 +224,32 @@ def conv_fwd_entries(g: ConvGeom, X, Wt, b, flat_index) -> np.ndarray:
     return out
 
 
+def bn_relu(Y, scale, shift) -> np.ndarray:
+    """relu(scale[c] * Y + shift[c]): a normalisation with given per-channel statistics followed by
+    the activation, i.e. what produces a convolution's input in the residual networks of the
+    experiments (architecture figure)."""
+    Y = _f64(Y)
+    sc, sh = _f64(scale)[None, :, None, None], _f64(shift)[None, :, None, None]
+    return np.maximum(sc * Y + sh, 0.0)
+
+
+def bn_bwd(Xsaved, dY, mean, invstd, gamma):
+    """Backward pass of y = gamma * xhat + beta, xhat = (x - mean) * invstd with batch statistics
+    (the textbook formulas), from the saved activation the backward pass has: x itself for the
+    exact step, the inflated record for the compressed one (the conclusion's extension of the
+    method to batch normalisation; a reading, the paper gives no formulas).
+    Returns (dgamma, dbeta, dX)."""
+    X, dY = _f64(Xsaved), _f64(dY)
+    N, C, H, W = X.shape
+    mu, istd, g = (_f64(v)[None, :, None, None] for v in (mean, invstd, gamma))
+    xh = (X - mu) * istd
+    M = N * H * W
+    dbeta = dY.sum(axis=(0, 2, 3))
+    dgamma = (dY * xh).sum(axis=(0, 2, 3))
+    dX = g * istd * (dY - dbeta[None, :, None, None] / M - xh * dgamma[None, :, None, None] / M)
+    return dgamma, dbeta, dX
+
+
 def bias_grad(dY) -> np.ndarray:
     dY = _f64(dY)
     N, K, P, Q = dY.shape

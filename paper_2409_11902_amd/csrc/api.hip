@@ -399,6 +399,38 @@ int conv_bwd_weight_and_data(const cac_desc *d, const void *Z, const void *W, co
     return launched(e, "data gradient");
 }
 
+int cac_bn_relu_fwd_compress(const cac_desc *d, const void *Y, const float *scale, const float *shift, void *X_next, void *Z_next,
+                             void *Z_in, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(Y, "Y")) || (rc = check_ptr(scale, "scale")) || (rc = check_ptr(shift, "shift")) ||
+        (rc = check_ptr(X_next, "X_next")) || (rc = check_ptr(Z_next, "Z_next")))
+        return rc;
+    if (Z_in && (rc = check_ptr(Z_in, "Z_in"))) return rc;
+    if (Y == X_next) return fail(CAC_ERR_INVALID_ARG, "X_next must not alias Y (tiles are read after their neighbours are written)");
+    hipError_t e = hipSuccess;
+    if (!launch_producer_fast(g, d->dtype, Y, scale, shift, X_next, Z_next, Z_in, (hipStream_t)stream, &e))
+        e = launch_producer_generic(g, d->dtype, Y, scale, shift, X_next, Z_next, Z_in, (hipStream_t)stream);
+    return launched(e, "normalise + activate + compress");
+}
+
+int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, const float *mean, const float *invstd,
+                          const float *gamma, float *dgamma, float *dbeta, void *dX, void *stream)
+{
+    Geom g;
+    int rc = make_geom(d, &g, true);
+    if (rc) return rc;
+    if ((rc = check_ptr(Z_in, "Z_in")) || (rc = check_ptr(dY, "dY")) || (rc = check_ptr(mean, "mean")) ||
+        (rc = check_ptr(invstd, "invstd")) || (rc = check_ptr(gamma, "gamma")) || (rc = check_ptr(dgamma, "dgamma")) ||
+        (rc = check_ptr(dbeta, "dbeta")) || (rc = check_ptr(dX, "dX")))
+        return rc;
+    if ((long)g.N * g.C > 65535L * 32767L) return fail(CAC_ERR_UNSUPPORTED, "N * C_in too large for this kernel's grid");
+    return launched(launch_bn_bwd(g, d->dtype, Z_in, dY, mean, invstd, gamma, dgamma, dbeta, dX, (hipStream_t)stream),
+                    "batch normalisation backward");
+}
+
 int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream)
 {
     Geom g;

@@ -64,6 +64,14 @@ hipError_t launch_fwd_generic(const Geom &g, int dtype, const void *X, const voi
 hipError_t launch_dx_generic(const Geom &g, int dtype, const void *W, const void *dY, void *dX, hipStream_t st);
 hipError_t launch_dw_generic(const Geom &g, int dtype, const void *Z, const void *dY, float *dW, hipStream_t st);
 hipError_t launch_db(const Geom &g, int dtype, const void *dY, float *db, hipStream_t st);
+// compress.hip / producer.hip: compression at the producer of the activation, and batch
+// normalisation's backward pass from its compressed saved input
+bool launch_producer_fast(const Geom &g, int dtype, const void *Y, const float *scale, const float *shift, void *Xn, void *Zn, void *Zin,
+                          hipStream_t st, hipError_t *err);
+hipError_t launch_producer_generic(const Geom &g, int dtype, const void *Y, const float *scale, const float *shift, void *Xn, void *Zn,
+                                   void *Zin, hipStream_t st);
+hipError_t launch_bn_bwd(const Geom &g, int dtype, const void *Zin, const void *dY, const float *mean, const float *invstd,
+                         const float *gamma, float *dgamma, float *dbeta, void *dX, hipStream_t st);
 // Buffer descriptor over a dense tensor of `bytes` bytes (raw, 32-bit elements): loads through
 // it return zero for every dword that does not lie entirely below the size, without touching
 // memory.  The size is rounded up to whole dwords: a tensor with an odd number of 2-byte

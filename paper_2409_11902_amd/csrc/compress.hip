@@ -63,31 +63,19 @@ template <> struct Chunk<float, 4> {
 // truncating absorbs the rounding of x * inv without ever reaching the next integer.
 __device__ __forceinline__ uint32_t udiv(uint32_t x, double inv) { return (uint32_t)((double)x * inv + 0x1p-18); }
 
+// What the producer form of the kernel does on top of compression (see launch_producer_fast).
+struct Producer {
+    const float *scale, *shift; // per channel
+    void *Xn;                   // relu(scale * X + shift), the next layer's input
+    void *Zin;                  // pooled X itself (the normalisation's own saved record), or null
+};
+
+// One chunk's pooled values: sums in row-then-column order; whole tiles multiply by the exact
+// reciprocal of their power-of-two count, ragged ones divide by the elements they really have.
 template <typename T, int EPC, int KH, int KW>
-__global__ void __launch_bounds__(256) compress_kernel(Geom g, const T *__restrict__ X, T *__restrict__ Z, int cpr,
-                                                       uint32_t total, double inv_cpr, double inv_hp)
+__device__ __forceinline__ void pool_and_store(const Geom &g, const float (&v)[KH][EPC], int rows, int w0, int j0, T *zrow)
 {
-    constexpr int OPC = EPC / KW; // pooled values per chunk
-    static_assert(OPC >= 1, "");
-    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
-    if (idx >= total) return;
-    // idx -> (plane, pooled row i, chunk c), chunk fastest
-    const uint32_t rowi = udiv(idx, inv_cpr);
-    const uint32_t c = idx - rowi * cpr;
-    const uint32_t plane = udiv(rowi, inv_hp);
-    const uint32_t i = rowi - plane * g.Hp;
-
-    const rsrc_t rs = make_rsrc(X, (uint32_t)g.N * g.C * g.H * g.W * (uint32_t)sizeof(T));
-    const int h0 = i * KH;
-    const int rows = min(KH, g.H - h0);
-    float v[KH][EPC];
-#pragma unroll
-    for (int a = 0; a < KH; ++a)
-        Chunk<T, EPC>::load(rs, (plane * g.H + h0 + a) * g.W + c * EPC, a < rows, g.W & 1, v[a]);
-
-    const int w0 = c * EPC;       // first input column of the chunk
-    const int j0 = c * OPC;       // first pooled column
-    T *zrow = Z + ((long)plane * g.Hp + i) * g.Wp;
+    constexpr int OPC = EPC / KW;
     const float inv_full = 1.0f / (float)(rows * KW); // exact for the power-of-two counts of whole tiles
     float res[OPC];
 #pragma unroll
@@ -129,20 +117,90 @@ __global__ void __launch_bounds__(256) compress_kernel(Geom g, const T *__restri
     }
 }
 
-template <typename T, int EPC> bool launch_epc(const Geom &g, const void *X, void *Z, hipStream_t st)
+template <typename T, int EPC, int KH, int KW, bool PROD>
+__global__ void __launch_bounds__(256) compress_kernel(Geom g, const T *__restrict__ X, T *__restrict__ Z, int cpr,
+                                                       uint32_t total, double inv_cpr, double inv_hp, Producer pr)
+{
+    constexpr int OPC = EPC / KW; // pooled values per chunk
+    static_assert(OPC >= 1, "");
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    // idx -> (plane, pooled row i, chunk c), chunk fastest
+    const uint32_t rowi = udiv(idx, inv_cpr);
+    const uint32_t c = idx - rowi * cpr;
+    const uint32_t plane = udiv(rowi, inv_hp);
+    const uint32_t i = rowi - plane * g.Hp;
+
+    const rsrc_t rs = make_rsrc(X, (uint32_t)g.N * g.C * g.H * g.W * (uint32_t)sizeof(T));
+    const int h0 = i * KH;
+    const int rows = min(KH, g.H - h0);
+    float v[KH][EPC];
+#pragma unroll
+    for (int a = 0; a < KH; ++a)
+        Chunk<T, EPC>::load(rs, (plane * g.H + h0 + a) * g.W + c * EPC, a < rows, g.W & 1, v[a]);
+
+    const int w0 = c * EPC;       // first input column of the chunk
+    const int j0 = c * OPC;       // first pooled column
+    const long zoff = ((long)plane * g.Hp + i) * g.Wp;
+    if constexpr (PROD) {
+        // the producer's own saved record: X pooled as it is
+        if (pr.Zin) pool_and_store<T, EPC, KH, KW>(g, v, rows, w0, j0, (T *)pr.Zin + zoff);
+        // the next layer's input, rounded to its storage type, and from those rounded values the
+        // next layer's pooled map (bit for bit what compressing the stored tensor would give)
+        const uint32_t ch = plane % (uint32_t)g.C;
+        const float sc = pr.scale[ch], sh = pr.shift[ch];
+        T *xn = (T *)pr.Xn;
+#pragma unroll
+        for (int a = 0; a < KH; ++a) {
+            if (a >= rows) continue;
+            const long e = ((long)plane * g.H + h0 + a) * g.W + w0;
+            const int left = g.W - w0;
+#pragma unroll
+            for (int b = 0; b < EPC; ++b) {
+                float y = fmaxf(fmaf(sc, v[a][b], sh), 0.f);
+                if constexpr (sizeof(T) == 2) y = bf16_to_f32(f32_to_bf16(y));
+                v[a][b] = y;
+            }
+            if (left >= EPC && ((e * sizeof(T)) & 15) == 0) {
+                if constexpr (sizeof(T) == 4) {
+                    *(u32x4 *)(xn + e) = u32x4{__float_as_uint(v[a][0]), __float_as_uint(v[a][1]), __float_as_uint(v[a][2]), __float_as_uint(v[a][3])};
+                } else if constexpr (EPC == 8) {
+                    u32x4 o;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) o[b] = (__float_as_uint(v[a][2 * b]) >> 16) | (__float_as_uint(v[a][2 * b + 1]) & 0xffff0000u);
+                    *(u32x4 *)(xn + e) = o;
+                } else {
+#pragma unroll
+                    for (int b = 0; b < EPC; ++b) Elem<T>::store(xn + e + b, v[a][b]);
+                }
+            } else {
+#pragma unroll
+                for (int b = 0; b < EPC; ++b)
+                    if (b < left) Elem<T>::store(xn + e + b, v[a][b]);
+            }
+        }
+    }
+    pool_and_store<T, EPC, KH, KW>(g, v, rows, w0, j0, Z + zoff);
+}
+
+template <typename T, int EPC> bool launch_epc(const Geom &g, const void *X, void *Z, hipStream_t st, const Producer *prod = nullptr)
 {
     const int cpr = (g.W + EPC - 1) / EPC;
     const long total = (long)g.N * g.C * g.Hp * cpr;
     if (total >= (1L << 31) || cpr >= (1 << 16) || g.Hp >= (1 << 16)) return false; // udiv's range
     const dim3 grid((unsigned)((total + 255) / 256));
-#define CAC_LAUNCH(KH, KW)                                                                                     \
-    hipLaunchKernelGGL((compress_kernel<T, EPC, KH, KW>), grid, dim3(256), 0, st, g, (const T *)X, (T *)Z, cpr, \
-                       (uint32_t)total, 1.0 / cpr, 1.0 / g.Hp)
-    if (g.kh == 2 && g.kw == 2) CAC_LAUNCH(2, 2);
-    else if (g.kh == 4 && g.kw == 4) CAC_LAUNCH(4, 4);
-    else if (g.kh == 1 && g.kw == 1) CAC_LAUNCH(1, 1);
-    else if (g.kh == 2 && g.kw == 4) CAC_LAUNCH(2, 4);
-    else if (g.kh == 4 && g.kw == 2) CAC_LAUNCH(4, 2);
+#define CAC_LAUNCH(KH, KW)                                                                                            \
+    if (prod)                                                                                                         \
+        hipLaunchKernelGGL((compress_kernel<T, EPC, KH, KW, true>), grid, dim3(256), 0, st, g, (const T *)X, (T *)Z, cpr, \
+                           (uint32_t)total, 1.0 / cpr, 1.0 / g.Hp, *prod);                                            \
+    else                                                                                                              \
+        hipLaunchKernelGGL((compress_kernel<T, EPC, KH, KW, false>), grid, dim3(256), 0, st, g, (const T *)X, (T *)Z, cpr, \
+                           (uint32_t)total, 1.0 / cpr, 1.0 / g.Hp, Producer{})
+    if (g.kh == 2 && g.kw == 2) { CAC_LAUNCH(2, 2); }
+    else if (g.kh == 4 && g.kw == 4) { CAC_LAUNCH(4, 4); }
+    else if (g.kh == 1 && g.kw == 1) { CAC_LAUNCH(1, 1); }
+    else if (g.kh == 2 && g.kw == 4) { CAC_LAUNCH(2, 4); }
+    else if (g.kh == 4 && g.kw == 2) { CAC_LAUNCH(4, 2); }
     else return false;
 #undef CAC_LAUNCH
     return true;
@@ -150,20 +208,34 @@ template <typename T, int EPC> bool launch_epc(const Geom &g, const void *X, voi
 
 } // namespace
 
-// True when the fast kernel covers the geometry (and has been launched).
-bool launch_compress_fast(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st, hipError_t *err)
+static bool launch_fast(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st, hipError_t *err, const Producer *prod)
 {
     if ((long)g.N * g.C * g.H * g.W * 4 >= (1L << 31)) return false; // 32-bit buffer offsets
     bool ok;
     if (dtype == CAC_F32) {
         if (g.kw > 4) return false;
-        ok = launch_epc<float, 4>(g, X, Z, st);
+        ok = launch_epc<float, 4>(g, X, Z, st, prod);
     } else {
         // narrow maps: 8-byte chunks so that a chunk does not span more than one row's worth
-        ok = g.W >= 8 ? launch_epc<bf16_t, 8>(g, X, Z, st) : (g.kw <= 4 ? launch_epc<bf16_t, 4>(g, X, Z, st) : false);
+        ok = g.W >= 8 ? launch_epc<bf16_t, 8>(g, X, Z, st, prod) : (g.kw <= 4 ? launch_epc<bf16_t, 4>(g, X, Z, st, prod) : false);
     }
     if (ok) *err = hipGetLastError();
     return ok;
+}
+
+// True when the fast kernel covers the geometry (and has been launched).
+bool launch_compress_fast(const Geom &g, int dtype, const void *X, void *Z, hipStream_t st, hipError_t *err)
+{
+    return launch_fast(g, dtype, X, Z, st, err, nullptr);
+}
+
+// The producer form: Xn = relu(scale[c] * Y + shift[c]) stored in the tensors' type, Zn = pooled Xn,
+// Zin (optional) = pooled Y, all from one read of Y.
+bool launch_producer_fast(const Geom &g, int dtype, const void *Y, const float *scale, const float *shift, void *Xn, void *Zn, void *Zin,
+                          hipStream_t st, hipError_t *err)
+{
+    const Producer prod{scale, shift, Xn, Zin};
+    return launch_fast(g, dtype, Y, Zn, st, err, &prod);
 }
 
 } // namespace cac

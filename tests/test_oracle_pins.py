@@ -317,6 +317,41 @@ def test_tile_sums_by_hand_and_by_mass():
             np.testing.assert_allclose(T.sum(axis=(2, 3)), dY2[:, :, rows][:, :, :, cols].sum(axis=(2, 3)), rtol=1e-13)
 
 
+# ---------------------------------------------------------------- normalisation at the producer
+
+def test_bn_backward_against_autograd_and_relu_form():
+    """The batch-normalisation backward formulas from the saved activation itself equal library
+    autograd through batch_norm in training mode; the producer's forward is the library's
+    batch_norm + relu when scale and shift are built from the batch statistics."""
+    rng = np.random.default_rng(5)
+    N, C, H, W = 3, 4, 5, 6
+    X = rng.standard_normal((N, C, H, W))
+    dY = rng.standard_normal((N, C, H, W))
+    gamma, beta = rng.standard_normal(C) + 1.5, rng.standard_normal(C)
+    eps = 1e-5
+    mean = X.mean(axis=(0, 2, 3))
+    var = X.var(axis=(0, 2, 3))
+    invstd = 1.0 / np.sqrt(var + eps)
+    xt = torch.tensor(X, requires_grad=True)
+    gt, bt = torch.tensor(gamma, requires_grad=True), torch.tensor(beta, requires_grad=True)
+    yt = F.batch_norm(xt, None, None, gt, bt, training=True, eps=eps)
+    yt.backward(torch.tensor(dY))
+    dgamma, dbeta, dX = oracle.bn_bwd(X, dY, mean, invstd, gamma)
+    np.testing.assert_allclose(dgamma, gt.grad.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dbeta, bt.grad.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dX, xt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    scale = gamma * invstd
+    shift = beta - mean * scale
+    np.testing.assert_allclose(oracle.bn_relu(X, scale, shift), F.relu(yt).detach().numpy(), rtol=1e-11, atol=1e-12)
+    # a tile-constant activation is its own inflated record: the compressed backward is then exact
+    Xc = np.repeat(np.repeat(rng.standard_normal((N, C, 3, 3)), 2, axis=2), 2, axis=3)[:, :, :5, :6]
+    Zc = oracle.avgpool(Xc, 2, 2)
+    a = oracle.bn_bwd(oracle.inflate(Zc, 5, 6, 2, 2), dY, mean, invstd, gamma)
+    b = oracle.bn_bwd(Xc, dY, mean, invstd, gamma)
+    for u, v in zip(a, b):
+        np.testing.assert_allclose(u, v, rtol=1e-12, atol=1e-12)
+
+
 # ---------------------------------------------------------------- sampled-entry functions
 
 @pytest.mark.parametrize("g", GEOMS[:4])
