@@ -233,7 +233,18 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
             B.cac_compress(L.d, xs[jt[0] % ncopy], L.Z, stream)
             jt[0] += 1
         r["cmp_cold_ms"] = timed(torch, stream, cmp_cold, 3 * ncopy, ncopy)
-        del xs
+        # compression at the producer: normalise + activate + pool in one pass over the same rotating inputs
+        Xn = torch.empty_like(L.X)
+        sc = torch.full((L.spec.C,), 1.25, dtype=torch.float32, device="cuda:0")
+        sh = torch.full((L.spec.C,), -0.1, dtype=torch.float32, device="cuda:0")
+        kt = [0]
+
+        def prod_cold():
+            B.cac_bn_relu_fwd_compress(L.d, xs[kt[0] % ncopy], sc, sh, Xn, L.Z, None, stream)
+            kt[0] += 1
+        r["prod_cold_ms"] = timed(torch, stream, prod_cold, 3 * ncopy, ncopy)
+        B.cac_compress(L.d, L.X, L.Z, stream)   # (Z of the layer's own input again)
+        del xs, Xn
         r["cos"] = grad_cosine(L, B, synth, torch, stream) if L.spec.dtype == synth.BF16 else (None, None)
         rows.append(r)
 
@@ -258,6 +269,9 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
              "fwd_compress_us": round(r["fwd_ms"] * 1e3, 2), "dx_us": round(r["dx_ms"] * 1e3, 2),
              "compress_cold_gbps": round(cg, 1), "compress_warm_gbps": round(wg, 1), "compress_bytes": L.bytes["compress"],
              "compress_cold_us": round(r["cmp_cold_ms"] * 1e3, 2),
+             # normalise + activate + pool fused at the producer: reads X once, writes X' and Z
+             "producer_fused_cold_us": round(r["prod_cold_ms"] * 1e3, 2),
+             "producer_fused_cold_gbps": round((2 * L.x_bytes + L.z_bytes) / (r["prod_cold_ms"] * 1e-3) / 1e9, 1),
              "x_bytes": L.x_bytes, "z_bytes": L.z_bytes, "saved_ratio": round(L.x_bytes / L.z_bytes, 3)}
         if rk:
             # the reduced-K form executes fewer multiply-adds for the same result: nominal flops
