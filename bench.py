@@ -303,6 +303,33 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
     return summary, layers, rows, graph is not None
 
 
+def measure_peaks(B, torch, stream):
+    """What this box attains on a bare MFMA loop (on random numbers and on zeros: the chip's clock
+    under sustained matrix load depends on the data) and on bare streams, with the library's
+    yardstick kernels; launches back to back like every other figure here."""
+    dev = "cuda:0"
+    out = {}
+    sink = torch.zeros(4096, dtype=torch.float32, device=dev)
+    iters = 400
+    flops = 2048 * iters * 16 * 2 * 32 * 32 * 16
+    for name, src in (("random", torch.randn(16384, dtype=torch.float32, device=dev).to(torch.bfloat16)),
+                      ("zeros", torch.zeros(16384, dtype=torch.bfloat16, device=dev))):
+        ms = timed(torch, stream, lambda: B.cac_probe(B.PROBE_MFMA, src, sink, src.numel() * 2, iters, stream), 200, 20)
+        out[f"mfma_bf16_tflops_{name}"] = round(flops / (ms * 1e-3) / 1e12, 1)
+    n = 512 << 20
+    a = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+    b = torch.empty(n, dtype=torch.uint8, device=dev)
+    ms = timed(torch, stream, lambda: B.cac_probe(B.PROBE_COPY, a, b, n, 0, stream), 20, 3)
+    out["hbm_copy_gbps"] = round(2 * n / (ms * 1e-3) / 1e9, 1)
+    ms = timed(torch, stream, lambda: B.cac_probe(B.PROBE_READ, a, sink, n, 0, stream), 20, 3)
+    out["hbm_read_gbps"] = round(n / (ms * 1e-3) / 1e9, 1)
+    out["note"] = ("bare 32x32x16 bf16 MFMA loop (2048 waves, 200 launches back to back) and 512 MiB streams on this box; "
+                   "data-sheet peaks: 2500 TFLOP/s, 8000 GB/s")
+    log(f"[bench] measured on this box: MFMA loop {out['mfma_bf16_tflops_random']} TFLOP/s on random numbers, "
+        f"{out['mfma_bf16_tflops_zeros']} on zeros; copy {out['hbm_copy_gbps']} GB/s, read {out['hbm_read_gbps']} GB/s")
+    return out
+
+
 def grad_cosine(L, B, synth, torch, stream):
     """Cosine similarity (the paper's layer-sensitivity metric) between the weight gradient
     computed from the pooled map and the exact one (the same call with pooling factor 1, whose
@@ -387,6 +414,10 @@ def main():
         layers = [Layer(s, args.workload, B, synth, torch) for s in specs]
         stream = torch.cuda.current_stream()
         for L in layers:
+            # Z from the library's own compress pass (an MFMA on all-zero operands runs faster than on data)
+            B.cac_compress(L.d, L.X, L.Z, stream)
+        torch.cuda.synchronize()
+        for L in layers:
             for _ in range(args.warmup + args.steps):
                 if args.only == "dw":
                     B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], stream)
@@ -402,6 +433,7 @@ def main():
         print(json.dumps({"only": args.only, "workload": args.workload, "calls_per_layer": args.warmup + args.steps}))
         return
 
+    peaks = measure_peaks(B, torch, torch.cuda.current_stream())
     head, layers, rows, graphed = measure_workload(args.workload, specs, args, B, synth, torch, np, detailed=True)
     for L in layers:
         log(f"[bench]   {L.spec.name}: {L.plan}")
@@ -432,13 +464,16 @@ def main():
         "roofline": {"kernel": f"conv_bwd_weight_compressed on {Ld.spec.name} (dw_mfma_kernel + dw_reduce)",
                      "bound": "mfma", "achieved": round(dom_tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4), "traffic": read_traffic(args.workload, Ld.spec.name),
+                     "frac_of_measured_mfma_loop": round(dom_tf / peaks["mfma_bf16_tflops_random"], 4),
                      "flops_per_launch": Ld.flops["dw"], "algorithmic_bytes_per_launch": Ld.bytes["dw"],
                      "avg_launch_us": round(rd["dw_ms"] * 1e3, 2), "avg_launch_us_cold": round(rd["dw_cold_ms"] * 1e3, 2),
                      "launches_timed": DW_LAUNCHES},
         "roofline_compress": {"kernel": f"compress_kernel (cac_compress) on {Lc.spec.name}, cold: inputs rotate through > 640 MB",
                               "bound": "hbm", "achieved": round(cmp_g, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                               "frac": round(cmp_g / PEAK_HBM_GBPS, 4), "bytes_per_launch": Lc.bytes["compress"],
+                              "frac_of_measured_read_stream": round(cmp_g / peaks["hbm_read_gbps"], 4),
                               "avg_launch_us": round(rc["cmp_cold_ms"] * 1e3, 2)},
+        "measured_peaks": peaks,
         "per_layer": head["per_layer"],
     }
     del layers, rows

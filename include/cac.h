@@ -236,6 +236,16 @@ int cac_bn_relu_fwd_compress(const cac_desc *d, const void *Y, const float *scal
 int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, const float *mean, const float *invstd,
                           const float *gamma, float *dgamma, float *dbeta, void *dX, void *stream);
 
+/* Yardsticks for benchmarks (no part of the method): what this machine attains on a bare
+ * matrix-core loop and on a bare stream, to set a kernel's rate against.
+ *   CAC_PROBE_MFMA: a grid of 2048 waves, each issuing iters * 16 independent 32x32x16 bfloat16
+ *                   MFMAs on fragments read once from src (at least 16 KiB; its VALUES matter: the
+ *                   chip clocks lower on random numbers than on zeros); 2*32*32*16 flops each.
+ *   CAC_PROBE_COPY: dst = src over `bytes` (a multiple of 16).   CAC_PROBE_READ: reads src.
+ * dst: at least 8 KiB for the first and last kind. */
+typedef enum cac_probe_kind { CAC_PROBE_MFMA = 0, CAC_PROBE_COPY = 1, CAC_PROBE_READ = 2 } cac_probe_kind;
+int cac_probe(int kind, const void *src, void *dst, size_t bytes, int iters, void *stream);
+
 /* Bias gradient (bias-gradient formula in the same figure): db[o] = sum_{n,p,q} dY.
  * db [C_out] float is overwritten. */
 int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream);

@@ -29,8 +29,9 @@ EXPORTS = (
     "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size", "cac_describe_plan",
     "cac_dw_executed_flops",
     "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias", "cac_grad_cosine",
-    "conv_bwd_weight_and_data", "conv_bwd_weight_compressed_noalloc", "cac_bn_relu_fwd_compress", "cac_bn_bwd_compressed",
+    "conv_bwd_weight_and_data", "conv_bwd_weight_compressed_noalloc", "cac_bn_relu_fwd_compress", "cac_bn_bwd_compressed", "cac_probe",
 )
+PROBE_MFMA, PROBE_COPY, PROBE_READ = 0, 1, 2
 NOALLOC_SCRATCH_BYTES = 40 << 20
 
 
@@ -78,6 +79,7 @@ def lib() -> ctypes.CDLL:
         L.conv_bwd_data.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_weight_and_data.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.conv_bwd_bias.argtypes = [dp, vp, vp, vp]
+        L.cac_probe.argtypes = [ctypes.c_int, vp, vp, sz, ctypes.c_int, vp]
         L.cac_bn_relu_fwd_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.cac_bn_bwd_compressed.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.cac_grad_cosine.argtypes = [dp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -199,6 +201,10 @@ def cac_bn_relu_fwd_compress(d, Y, scale, shift, X_next, Z_next, Z_in=None, stre
 def cac_bn_bwd_compressed(d, Z_in, dY, mean, invstd, gamma, dgamma, dbeta, dX, stream=None):
     _check(lib().cac_bn_bwd_compressed(ctypes.byref(d), _ptr(Z_in), _ptr(dY), _ptr(mean), _ptr(invstd), _ptr(gamma),
                                        _ptr(dgamma), _ptr(dbeta), _ptr(dX), _stream(stream)))
+
+
+def cac_probe(kind, src, dst, nbytes, iters=0, stream=None):
+    _check(lib().cac_probe(kind, _ptr(src), _ptr(dst), nbytes, iters, _stream(stream)))
 
 
 def conv_bwd_bias(d, dY, db, stream=None):

@@ -83,6 +83,9 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (bytes + 3u) & ~3u, 0x00020000);
 }
 
+// probe.hip: the benchmark's yardstick kernels
+hipError_t launch_probe(int kind, const void *src, void *dst, size_t bytes, int iters, hipStream_t st);
+
 size_t cosine_workspace(long n);
 hipError_t launch_cosine(const float *a, const float *b, long n, float *out, void *ws, hipStream_t st);
 
