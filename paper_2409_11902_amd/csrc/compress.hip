@@ -68,6 +68,7 @@ struct Producer {
     const float *scale, *shift; // per channel
     void *Xn;                   // relu(scale * X + shift), the next layer's input
     void *Zin;                  // pooled X itself (the normalisation's own saved record), or null
+    double inv_c;               // 1 / channels
 };
 
 // One chunk's pooled values: sums in row-then-column order; whole tiles multiply by the exact
@@ -147,36 +148,54 @@ __global__ void __launch_bounds__(256) compress_kernel(Geom g, const T *__restri
         if (pr.Zin) pool_and_store<T, EPC, KH, KW>(g, v, rows, w0, j0, (T *)pr.Zin + zoff);
         // the next layer's input, rounded to its storage type, and from those rounded values the
         // next layer's pooled map (bit for bit what compressing the stored tensor would give)
-        const uint32_t ch = plane % (uint32_t)g.C;
+        const uint32_t ch = plane - udiv(plane, pr.inv_c) * (uint32_t)g.C;
         const float sc = pr.scale[ch], sh = pr.shift[ch];
         T *xn = (T *)pr.Xn;
+        typedef u32x4 __attribute__((aligned(4))) u32x4_u;
 #pragma unroll
         for (int a = 0; a < KH; ++a) {
             if (a >= rows) continue;
             const long e = ((long)plane * g.H + h0 + a) * g.W + w0;
             const int left = g.W - w0;
+            if constexpr (sizeof(T) == 4) {
 #pragma unroll
-            for (int b = 0; b < EPC; ++b) {
-                float y = fmaxf(fmaf(sc, v[a][b], sh), 0.f);
-                if constexpr (sizeof(T) == 2) y = bf16_to_f32(f32_to_bf16(y));
-                v[a][b] = y;
-            }
-            if (left >= EPC && ((e * sizeof(T)) & 15) == 0) {
-                if constexpr (sizeof(T) == 4) {
-                    *(u32x4 *)(xn + e) = u32x4{__float_as_uint(v[a][0]), __float_as_uint(v[a][1]), __float_as_uint(v[a][2]), __float_as_uint(v[a][3])};
-                } else if constexpr (EPC == 8) {
-                    u32x4 o;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) o[b] = (__float_as_uint(v[a][2 * b]) >> 16) | (__float_as_uint(v[a][2 * b + 1]) & 0xffff0000u);
-                    *(u32x4 *)(xn + e) = o;
+                for (int b = 0; b < EPC; ++b) v[a][b] = fmaxf(fmaf(sc, v[a][b], sh), 0.f);
+                if (left >= EPC) { // (float rows start on dwords: a 16-byte global store only needs that)
+                    *(u32x4_u *)(xn + e) = u32x4{__float_as_uint(v[a][0]), __float_as_uint(v[a][1]), __float_as_uint(v[a][2]), __float_as_uint(v[a][3])};
                 } else {
 #pragma unroll
-                    for (int b = 0; b < EPC; ++b) Elem<T>::store(xn + e + b, v[a][b]);
+                    for (int b = 0; b < EPC; ++b)
+                        if (b < left) xn[e + b] = v[a][b];
                 }
             } else {
+                // pairs rounded by the hardware conversion (round to nearest even); the pooled map is
+                // formed from the rounded values
+                uint32_t o[EPC / 2];
 #pragma unroll
-                for (int b = 0; b < EPC; ++b)
-                    if (b < left) Elem<T>::store(xn + e + b, v[a][b]);
+                for (int b = 0; b < EPC / 2; ++b) {
+                    o[b] = f32x2_to_bf16x2(fmaxf(fmaf(sc, v[a][2 * b], sh), 0.f), fmaxf(fmaf(sc, v[a][2 * b + 1], sh), 0.f));
+                    v[a][2 * b] = __uint_as_float(o[b] << 16);
+                    v[a][2 * b + 1] = __uint_as_float(o[b] & 0xffff0000u);
+                }
+                if ((e & 1) == 0) {
+                    // the chunk starts on a dword (every row of an even W does): global stores of several
+                    // dwords only need that alignment
+                    if (EPC == 8 && left >= 8) {
+                        *(u32x4_u *)(xn + e) = u32x4{o[0], o[1], o[EPC / 4], o[EPC / 2 - 1]};
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < EPC / 2; ++b) {
+                            if (2 * b + 1 < left)
+                                *(uint32_t *)(xn + e + 2 * b) = o[b];
+                            else if (2 * b < left)
+                                xn[e + 2 * b] = (bf16_t)(o[b] & 0xffffu);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int b = 0; b < EPC; ++b)
+                        if (b < left) xn[e + b] = (bf16_t)((b & 1) ? o[b / 2] >> 16 : o[b / 2] & 0xffffu);
+                }
             }
         }
     }
@@ -234,7 +253,7 @@ bool launch_compress_fast(const Geom &g, int dtype, const void *X, void *Z, hipS
 bool launch_producer_fast(const Geom &g, int dtype, const void *Y, const float *scale, const float *shift, void *Xn, void *Zn, void *Zin,
                           hipStream_t st, hipError_t *err)
 {
-    const Producer prod{scale, shift, Xn, Zin};
+    const Producer prod{scale, shift, Xn, Zin, 1.0 / g.C};
     return launch_fast(g, dtype, Y, Zn, st, err, &prod);
 }
 
