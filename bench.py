@@ -548,12 +548,20 @@ def cpu_baseline(specs, config, synth, seconds, np):
         return {"value": round(flops / t_total / 1e12, 5), "unit": unit, "cores": oracle.num_threads(), "kind": "oracle",
                 "sample": f"one step over the first {done} of {len(specs)} layers of {config} (forward, pooling, "
                           f"inflation, dW, dX of each whole layer), fp64 direct loops, {t_total:.1f}s"}
-    # sampled outputs: a third of the time budget each
+    # sampled outputs: a third of the time budget each, every count sized by a probe of its own
     per_dw = 2.0 * spec.N * spec.P * spec.Q
     per_y = 2.0 * spec.C * spec.R * spec.S
-    n_dw = int(min(total, max(256, seconds / 3 * flops_per_s / per_dw)))
-    n_y = int(min(spec.N * spec.K * spec.P * spec.Q, n_dw * per_dw / per_y))
-    n_x = int(min(spec.N * spec.C * spec.H * spec.W, n_y))
+    n_all_y, n_all_x = spec.N * spec.K * spec.P * spec.Q, spec.N * spec.C * spec.H * spec.W
+
+    def sized(fn, n_probe, n_all):
+        t0 = time.perf_counter()
+        fn(n_probe)
+        per_entry = (time.perf_counter() - t0) / n_probe
+        return int(min(n_all, max(n_probe, seconds / 3 / max(per_entry, 1e-12))))
+
+    n_dw = sized(lambda n: oracle.conv_dw_entries(g, Xh, dY, rng.integers(0, total, n)), 4096, total)
+    n_y = sized(lambda n: oracle.conv_fwd_entries(g, X, W, b, rng.integers(0, n_all_y, n)), 65536, n_all_y)
+    n_x = sized(lambda n: oracle.conv_dx_entries(g, W, dY, rng.integers(0, n_all_x, n)), 65536, n_all_x)
     t0 = time.perf_counter()
     oracle.conv_dw_entries(g, Xh, dY, rng.integers(0, total, n_dw))
     t_dw = time.perf_counter() - t0
