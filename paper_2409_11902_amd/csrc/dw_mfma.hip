@@ -519,8 +519,13 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             if (!(have_blk0 && S > 1)) o.aw[mi].blk[0] = lds16(ra + mi * astep + 16 * seg);
-            if constexpr (S > 1) // the dynamic LDS block starts with the zero row
-                o.aw[mi].blk[1] = lds16(tail ? lds0 : ra + mi * astep + 16 * seg + 16);
+            if constexpr (S > 1) {
+                // nothing lies right of a row's last segment.  Where the caller knows at compile
+                // time that this is one, the block is a constant; otherwise it is read from the
+                // zero row the dynamic LDS block starts with.
+                if (__builtin_constant_p(tail) && tail) o.aw[mi].blk[1] = u32x4{0, 0, 0, 0};
+                else o.aw[mi].blk[1] = lds16(tail ? lds0 : ra + mi * astep + 16 * seg + 16);
+            }
         }
 #pragma unroll
         for (int r = 0; r < R; ++r)
