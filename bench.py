@@ -56,8 +56,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-backward", action="store_true",
                     help="the step calls conv_bwd_weight_compressed and conv_bwd_data instead of conv_bwd_weight_and_data")
-    ap.add_argument("--dw-algo", default="inflate", choices=["inflate", "reduced_k"],
-                    help="weight-gradient kernel of the step: the one that inflates Z in LDS (default) or the reduced-K form")
+    ap.add_argument("--dw-algo", default="inflate", choices=["inflate", "reduced_k", "auto"],
+                    help="weight-gradient kernel of the step: the one that inflates Z in LDS (default), the reduced-K form "
+                         "wherever it exists, or the reduced-K form where it pays (auto)")
     ap.add_argument("--only", default="", choices=["", "dw", "dw_rk", "compress", "fwd", "dx", "copy"],
                     help="profiling aid: run just this entry point --steps times per layer (after --warmup untimed ones) "
                          "and exit (copy: a plain 256 MiB device copy, the yardstick the HBM counters are scaled by)")
@@ -103,6 +104,7 @@ class Layer:
         self.spec = spec
         self.d = B.desc_from_spec(spec, dw_algo=dw_algo)
         self.d_rk = B.desc_from_spec(spec, dw_algo=B.DW_REDUCED_K)
+        self.d_auto = B.desc_from_spec(spec, dw_algo=B.DW_AUTO)
         self.has_rk = B.cac_describe_plan(self.d_rk, B.OP_BWD_WEIGHT_COMPRESSED).startswith("dw_rk")
         hp, wp, self.z_bytes, self.x_bytes = B.cac_pooled_shape(self.d)
         td = torch.float32 if spec.dtype == synth.F32 else torch.bfloat16
@@ -148,57 +150,65 @@ def timed(torch, stream, fn, n, warm):
 def measure_workload(name, specs, args, B, synth, torch, np, detailed):
     """Sets the workload's layers up, times one step (HIP graph) and every entry point per layer."""
     t0 = time.time()
-    algo = B.DW_REDUCED_K if args.dw_algo == "reduced_k" else B.DW_INFLATE
+    algo = {"reduced_k": B.DW_REDUCED_K, "auto": B.DW_AUTO}.get(args.dw_algo, B.DW_INFLATE)
     layers = [Layer(s, name, B, synth, torch, dw_algo=algo) for s in specs]
     torch.cuda.synchronize()
     log(f"[bench] {name}: {len(layers)} layers set up in {time.time() - t0:.1f}s")
     stream = torch.cuda.current_stream()
 
-    def step(st):
+    def step(st, auto=False):
         for L in layers:
-            B.conv_fwd_and_compress(L.d, L.X, L.W, L.b, L.Y, L.Z, L.ws[B.OP_FWD_AND_COMPRESS], st)
+            d = L.d_auto if auto else L.d
+            B.conv_fwd_and_compress(d, L.X, L.W, L.b, L.Y, L.Z, L.ws[B.OP_FWD_AND_COMPRESS], st)
             if args.separate_backward:
-                B.conv_bwd_weight_compressed(L.d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], st)
-                B.conv_bwd_data(L.d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], st)
+                B.conv_bwd_weight_compressed(d, L.Z, L.dY, L.dW, L.ws[B.OP_BWD_WEIGHT_COMPRESSED], st)
+                B.conv_bwd_data(d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], st)
             else:
                 # both gradients of the layer in one call (same kernels and results; one launch fewer)
-                B.conv_bwd_weight_and_data(L.d, L.Z, L.W, L.dY, L.dW, L.dX, L.ws[B.OP_BWD_WEIGHT_AND_DATA], st)
+                B.conv_bwd_weight_and_data(d, L.Z, L.W, L.dY, L.dW, L.dX, L.ws[B.OP_BWD_WEIGHT_AND_DATA], st)
 
-    # ---- untimed warm-up (also sets kernel attributes before any capture)
-    for _ in range(max(1, args.warmup if detailed else 2)):
-        step(stream)
-    torch.cuda.synchronize()
-    graph = None
-    if not args.no_graph:
-        try:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                step(side)
+    def time_step(auto):
+        """ms per step (HIP graph replays where capture works) and whether a graph was used."""
+        # ---- untimed warm-up (also sets kernel attributes before any capture)
+        for _ in range(max(1, args.warmup if detailed else 2)):
+            step(stream, auto)
+        torch.cuda.synchronize()
+        graph = None
+        if not args.no_graph:
+            try:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    step(side, auto)
+                    torch.cuda.synchronize()
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side):
+                        step(side, auto)
                 torch.cuda.synchronize()
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g, stream=side):
-                    step(side)
-            torch.cuda.synchronize()
-            ref = [L.dW.clone() for L in layers]
-            for _ in range(3):
-                g.replay()
-            torch.cuda.synchronize()
-            assert all(torch.equal(r, L.dW) for r, L in zip(ref, layers)), "graph replay changed dW"
-            graph = g
-        except Exception as e:  # capture is an optimisation of the launch path only
-            log(f"[bench] HIP graph capture unavailable ({type(e).__name__}: {e}); launching eagerly")
-            graph = None
-    run = (lambda: graph.replay()) if graph is not None else (lambda: step(stream))
-    steps, warm = (args.steps, args.warmup) if detailed else (max(5, min(args.steps, 20)), 3)
-    for _ in range(warm):
-        run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        run()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+                ref = [L.dW.clone() for L in layers]
+                for _ in range(3):
+                    g.replay()
+                torch.cuda.synchronize()
+                assert all(torch.equal(r, L.dW) for r, L in zip(ref, layers)), "graph replay changed dW"
+                graph = g
+            except Exception as e:  # capture is an optimisation of the launch path only
+                log(f"[bench] HIP graph capture unavailable ({type(e).__name__}: {e}); launching eagerly")
+                graph = None
+        run = (lambda: graph.replay()) if graph is not None else (lambda: step(stream, auto))
+        steps, warm = (args.steps, args.warmup) if detailed else (max(5, min(args.steps, 20)), 3)
+        for _ in range(warm):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3, graph is not None
+
+    ms_per_step, graphed_step = time_step(False)
+    # the same step with dw_algo = AUTO: the reduced-K weight gradient on the layers where it pays
+    on_rk = [L.spec.name for L in layers if B.cac_describe_plan(L.d_auto, B.OP_BWD_WEIGHT_COMPRESSED).startswith("dw_rk")]
+    ms_per_step_auto = time_step(True)[0] if (on_rk and algo == B.DW_INFLATE) else None
 
     rows = []
     for L in layers:
@@ -248,7 +258,7 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
         r["cos"] = grad_cosine(L, B, synth, torch, stream) if L.spec.dtype == synth.BF16 else (None, None)
         rows.append(r)
 
-    log(f"[bench] {name}: step {ms_per_step:.3f} ms ({'hip graph' if graph is not None else 'eager'})")
+    log(f"[bench] {name}: step {ms_per_step:.3f} ms ({'hip graph' if graphed_step else 'eager'})")
     log(f"[bench] {'layer':30s} {'k':>2s} {'fwd+cmp us':>10s} {'dW us':>8s} {'cold us':>8s} {'TF/s':>7s} {'roof':>4s} {'%roof':>6s} "
         f"{'rk us':>7s} {'dX us':>8s} {'cmp cold GB/s':>13s} {'%hbm':>5s} {'X MiB':>7s} {'Z MiB':>7s} {'saved':>6s} {'cos':>6s}")
     per_layer = []
@@ -292,7 +302,7 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
     summary = {
         "workload": name, "dtype": "bf16" if specs[0].dtype == synth.BF16 else "f32", "batch": specs[0].N, "pool_k": specs[0].k,
         "ms_per_step": round(ms_per_step, 4), "step_tflops": round(tot_flops / (ms_per_step * 1e-3) / 1e12, 2),
-        "launch": "hip_graph" if graph is not None else "eager",
+        "launch": "hip_graph" if graphed_step else "eager",
         "dw_tflops": round(dw_flops / (dw_ms * 1e-3) / 1e12, 1),
         "dw_frac_of_binding_roof": round(sum(L.dw_tmin_us for L in layers) / (dw_ms * 1e3), 4),
         "compress_cold_gbps": round(comp_bytes / (comp_ms * 1e-3) / 1e9, 1),
@@ -300,7 +310,12 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
         "activation_bytes": {"x": x_total, "z": z_total, "saved": x_total - z_total, "ratio": round(x_total / z_total, 3)},
         "per_layer": per_layer,
     }
-    return summary, layers, rows, graph is not None
+    if ms_per_step_auto is not None:
+        # same dW within the storage rounding of the tile sums; nominal = the definition's flops over the time
+        summary["step_dw_auto"] = {"ms_per_step": round(ms_per_step_auto, 4),
+                                   "step_tflops_nominal": round(tot_flops / (ms_per_step_auto * 1e-3) / 1e12, 2),
+                                   "layers_on_reduced_k": on_rk}
+    return summary, layers, rows, graphed_step
 
 
 def measure_peaks(B, torch, stream):
@@ -476,6 +491,8 @@ def main():
         "measured_peaks": peaks,
         "per_layer": head["per_layer"],
     }
+    if "step_dw_auto" in head:
+        out["step_dw_auto"] = head["step_dw_auto"]
     del layers, rows
     torch.cuda.empty_cache()
 
@@ -496,6 +513,14 @@ def main():
         if big:
             gb = sum(e["compress_bytes"] for e in big) / sum(e["compress_cold_us"] for e in big) / 1e3
             out["compress_large_tensors"] = {"tensors": len(big), "cold_gbps": round(gb, 1), "frac_of_hbm_peak": round(gb / PEAK_HBM_GBPS, 4)}
+            # and on the largest single tensor of the run, with the workload it belongs to
+            wl, top = max(((w, e) for w, r in list(results.items()) + [(args.workload, head)] for e in r["per_layer"]),
+                          key=lambda we: we[1]["x_bytes"])
+            out["roofline_compress_largest_tensor"] = {
+                "kernel": f"compress_kernel (cac_compress) on {top['layer']} of {wl}, cold", "bound": "hbm",
+                "achieved": top["compress_cold_gbps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": round(top["compress_cold_gbps"] / PEAK_HBM_GBPS, 4), "bytes_per_launch": top["compress_bytes"],
+                "avg_launch_us": top["compress_cold_us"]}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.workload, synth, args.cpu_seconds, np)

@@ -48,7 +48,7 @@
 extern "C" {
 #endif
 
-#define CAC_VERSION 300 /* major*10000 + minor*100 + patch */
+#define CAC_VERSION 301 /* major*10000 + minor*100 + patch */
 
 typedef enum cac_status {
     CAC_OK = 0,
@@ -92,8 +92,11 @@ typedef enum cac_pool_mode { CAC_POOL_MEAN = 0, CAC_POOL_MAX = 1 } cac_pool_mode
  *                                 floor((p*stride_h+r-pad_h)/kh) = i, floor((q*stride_w+s-pad_w)/kw) = j.
  *               kh*kw times fewer multiply-adds.  S is formed in float and rounded to bfloat16
  *               once (one more storage rounding of the same size as Z's own).  Layers this
- *               version has no such kernel for (cac_describe_plan tells) run as INFLATE. */
-typedef enum cac_dw_algo { CAC_DW_INFLATE = 0, CAC_DW_REDUCED_K = 1 } cac_dw_algo;
+ *               version has no such kernel for (cac_describe_plan tells) run as INFLATE.
+ *   AUTO      : REDUCED_K where that kernel exists for the layer and the layer is large enough
+ *               for it to be the faster one (about 24 GFLOP of nominal work per call), else
+ *               INFLATE.  cac_describe_plan tells which. */
+typedef enum cac_dw_algo { CAC_DW_INFLATE = 0, CAC_DW_REDUCED_K = 1, CAC_DW_AUTO = 2 } cac_dw_algo;
 
 typedef enum cac_op {
     CAC_OP_FWD_AND_COMPRESS = 0,

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libcac.so")
 CAC_OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_ALIGNMENT, ERR_LAUNCH_FAILED = -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-DW_INFLATE, DW_REDUCED_K = 0, 1
+DW_INFLATE, DW_REDUCED_K, DW_AUTO = 0, 1, 2
 EDGE_CEIL_VALID, EDGE_FLOOR_DROP = 0, 1
 POOL_MEAN, POOL_MAX = 0, 1
 (OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS, OP_GRAD_COSINE,

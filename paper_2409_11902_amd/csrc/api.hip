@@ -49,7 +49,7 @@ static int make_geom(const cac_desc *d, Geom *g, bool for_kernel)
     if (d->pad_h < 0 || d->pad_w < 0) return fail(CAC_ERR_INVALID_ARG, "padding must be non-negative");
     if (d->pool_kh <= 0 || d->pool_kw <= 0) return fail(CAC_ERR_INVALID_ARG, "pooling tile must be positive");
     if (d->dtype != CAC_F32 && d->dtype != CAC_BF16) return fail(CAC_ERR_INVALID_ARG, "unknown dtype %d", d->dtype);
-    if (d->dw_algo != CAC_DW_INFLATE && d->dw_algo != CAC_DW_REDUCED_K)
+    if (d->dw_algo != CAC_DW_INFLATE && d->dw_algo != CAC_DW_REDUCED_K && d->dw_algo != CAC_DW_AUTO)
         return fail(CAC_ERR_INVALID_ARG, "unknown dw_algo %d", d->dw_algo);
     if (d->edge_mode != CAC_EDGE_CEIL_VALID && d->edge_mode != CAC_EDGE_FLOOR_DROP)
         return fail(CAC_ERR_INVALID_ARG, "unknown edge_mode %d", d->edge_mode);
@@ -109,6 +109,22 @@ static size_t workspace_bytes(const Geom &g, int dtype, int op);
 
 // Part of the combined backward call's workspace that the weight gradient uses (the data
 // gradient's part starts behind it, 256-byte aligned).
+// The reduced-K kernel's plan when the descriptor asks for that form and the kernel covers the
+// geometry.  AUTO asks for it only where it has measured faster than the inflating kernel: from
+// about 24 GFLOP of nominal work per call on.  Below that the two finish within a few microseconds
+// of each other or the inflating kernel wins (a workgroup of the reduced-K kernel forms the tile
+// sums of its 32 output channels for only 128 input channels, and its partial sums are larger).
+static bool reduced_k_plan(const Geom &g, int dtype, DwRkPlan *rk)
+{
+    if (g.dw_algo != CAC_DW_REDUCED_K && g.dw_algo != CAC_DW_AUTO) return false;
+    if (!dw_rk_plan(g, dtype, rk)) return false;
+    if (g.dw_algo == CAC_DW_AUTO) {
+        const double nominal = 2.0 * g.N * g.P * g.Q * (double)g.K * g.C * g.R * g.S;
+        if (nominal < 24e9) return false;
+    }
+    return true;
+}
+
 static size_t both_dw_bytes(const Geom &g, int dtype)
 {
     return (workspace_bytes(g, dtype, CAC_OP_BWD_WEIGHT_COMPRESSED) + 255) & ~(size_t)255;
@@ -118,7 +134,7 @@ static size_t workspace_bytes(const Geom &g, int dtype, int op)
 {
     if (op == CAC_OP_BWD_WEIGHT_COMPRESSED) {
         DwRkPlan rk;
-        if (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, dtype, &rk)) return rk.partial_bytes;
+        if (reduced_k_plan(g, dtype, &rk)) return rk.partial_bytes;
         DwMfmaPlan plan;
         if (dw_mfma_plan(g, dtype, &plan)) return plan.partial_bytes; // partial sums of the pixel slices
         DwTiledPlan tl;
@@ -159,7 +175,7 @@ static int launch_weight_gradient(const Geom &g, int dtype, const void *Z, const
 {
     if (defer) defer->blocks = 0;
     DwRkPlan rk;
-    if (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, dtype, &rk))
+    if (reduced_k_plan(g, dtype, &rk))
         return launched(launch_dw_rk(rk, Z, dY, dW, ws, st, defer), "weight gradient (reduced K)");
     DwMfmaPlan plan;
     if (dw_mfma_plan(g, dtype, &plan)) return launched(launch_dw_mfma(plan, Z, dY, dW, ws, st, defer), "weight gradient (MFMA)");
@@ -252,7 +268,7 @@ int cac_dw_executed_flops(const cac_desc *d, uint64_t *flops)
     if (rc) return rc;
     if (!flops) return fail(CAC_ERR_INVALID_ARG, "flops is NULL");
     DwRkPlan rk;
-    if (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, d->dtype, &rk))
+    if (reduced_k_plan(g, d->dtype, &rk))
         *flops = rk.executed_flops;
     else
         *flops = 2ull * g.N * g.P * g.Q * (uint64_t)g.K * g.C * g.R * g.S;
@@ -268,7 +284,7 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
     if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_WEIGHT_AND_DATA) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     DwMfmaPlan plan;
     DwRkPlan rk;
-    if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, d->dtype, &rk)) {
+    if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && reduced_k_plan(g, d->dtype, &rk)) {
         const DwRkParams &p = rk.p;
         snprintf(buf, buf_len,
                  "dw_rk tile=32x128 unit=%dimg x %dpooled rows (Z rows %d, tile-sum rows %d, blocks %d/%d) chunk=2 units "
@@ -293,7 +309,7 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
         snprintf(buf, buf_len, "streaming kernel");
     } else if (op == CAC_OP_BWD_WEIGHT_AND_DATA) {
         char dx[64];
-        const bool split = (g.dw_algo == CAC_DW_REDUCED_K && dw_rk_plan(g, d->dtype, &rk)) ? !rk.p.direct
+        const bool split = (reduced_k_plan(g, d->dtype, &rk)) ? !rk.p.direct
                                                                                            : (dw_mfma_plan(g, d->dtype, &plan) && !plan.p.direct);
         const bool merged = split && describe_conv_mfma(g, d->dtype, true, dx, sizeof dx);
         snprintf(buf, buf_len, merged ? "weight gradient, then its slice sum in the launch of the data gradient's repack, then the data gradient"

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert B.cac_version() == 300
+    assert B.cac_version() == 301
 
 
 def test_desc_layout_matches_header():
@@ -92,7 +92,7 @@ def _expect(code, fn, *a):
 def test_invalid_descriptors_are_rejected():
     good = dict(N=2, C_in=4, C_out=4, H=8, W=8, R=3, S=3, pad_h=1, pad_w=1)
     for bad in (dict(N=0), dict(C_in=-1), dict(H=0), dict(R=0), dict(stride_h=0), dict(pad_w=-1),
-                dict(pool_kh=0), dict(dtype=7), dict(dw_algo=2), dict(edge_mode=3), dict(pool_mode=2), dict(pool_mode=-1),
+                dict(pool_kh=0), dict(dtype=7), dict(dw_algo=3), dict(edge_mode=3), dict(pool_mode=2), dict(pool_mode=-1),
                 dict(R=11, pad_h=0)):
         d = B.make_desc(**{**good, **bad})
         _expect(B.ERR_INVALID_ARG, B.cac_pooled_shape, d)
@@ -222,3 +222,24 @@ def test_benchmark_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stderr + r.stdout) and r.stdout.strip() == ""
+
+
+def test_auto_weight_gradient_picks_by_layer_size():
+    """dw_algo = AUTO: the reduced-K kernel on the large even-map 3x3 layers, the inflating one on
+    small layers and wherever the reduced-K kernel does not exist (the plan string tells)."""
+    cfg = synth.configs()
+    def plan(spec, algo):
+        return B.cac_describe_plan(B.desc_from_spec(spec, dw_algo=algo), B.OP_BWD_WEIGHT_COMPRESSED)
+    big, odd = cfg["cfg5_deep_small_spatial"]
+    assert plan(big, B.DW_AUTO).startswith("dw_rk") and plan(big, B.DW_AUTO) == plan(big, B.DW_REDUCED_K)
+    assert plan(odd, B.DW_AUTO) == plan(odd, B.DW_INFLATE)
+    small = cfg["cfg2_resnet18_cifar"][1]
+    assert plan(small, B.DW_REDUCED_K).startswith("dw_rk")
+    assert plan(small, B.DW_AUTO) == plan(small, B.DW_INFLATE)
+    for algo in (B.DW_INFLATE, B.DW_AUTO):
+        d = B.desc_from_spec(small, dw_algo=algo)
+        assert B.dw_rk_executed_flops(d) == small.dw_flops
+    d = B.desc_from_spec(big, dw_algo=B.DW_AUTO)
+    assert B.dw_rk_executed_flops(d) * 4 == big.dw_flops
+    assert B.cac_workspace_size(d, B.OP_BWD_WEIGHT_COMPRESSED) == \
+        B.cac_workspace_size(B.desc_from_spec(big, dw_algo=B.DW_REDUCED_K), B.OP_BWD_WEIGHT_COMPRESSED)

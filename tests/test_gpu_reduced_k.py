@@ -139,3 +139,26 @@ def test_reduced_k_in_the_combined_backward_call():
         b.check("rk both")
     assert torch.equal(dW1.t, dW2.t)
     assert torch.equal(dX1.t.view(torch.int16), dX2.t.view(torch.int16))
+
+
+def test_auto_runs_the_kernel_its_plan_names():
+    """dw_algo = AUTO: bit for bit the reduced-K result on a layer large enough for it, the
+    inflating kernel's on a small one."""
+    from gpu_util import Guarded, upload, workspace
+    cfg = synth.configs()
+    for config, spec, same_as in (("cfg5_deep_small_spatial", cfg["cfg5_deep_small_spatial"][0], B.DW_REDUCED_K),
+                                  ("cfg2_resnet18_cifar", cfg["cfg2_resnet18_cifar"][1], B.DW_INFLATE)):
+        t = synth.make_inputs(spec, config, tensors=("X", "dY"))
+        X, dY = upload(t["X"], spec.dtype), upload(t["dY"], spec.dtype)
+        da, db = B.desc_from_spec(spec, dw_algo=B.DW_AUTO), B.desc_from_spec(spec, dw_algo=same_as)
+        hp, wp, _, _ = B.cac_pooled_shape(da)
+        Z = torch.empty((spec.N, spec.C, hp, wp), dtype=torch.bfloat16, device="cuda:0")
+        B.cac_compress(da, X, Z)
+        shape = (spec.K, spec.C, spec.R, spec.S)
+        dWa, dWb = Guarded(shape, torch.float32), Guarded(shape, torch.float32)
+        B.conv_bwd_weight_compressed(da, Z, dY, dWa.t, workspace(da, B.OP_BWD_WEIGHT_COMPRESSED))
+        B.conv_bwd_weight_compressed(db, Z, dY, dWb.t, workspace(db, B.OP_BWD_WEIGHT_COMPRESSED))
+        torch.cuda.synchronize()
+        dWa.check(spec.name)
+        dWb.check(spec.name)
+        assert torch.equal(dWa.t, dWb.t), spec.name
