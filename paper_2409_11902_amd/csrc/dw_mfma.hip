@@ -541,6 +541,52 @@ __global__ void __launch_bounds__(128 * WM * WN * KS) dw_mfma_kernel(DwMfmaParam
         const uint32_t tab = lds0 + 2 * base + half * 16; // row table, this half-wave's entries
         // the KS waves that share a tile take every KS-th row pair each
         const int nrp = p.LRpad / 2, segs = SC > 0 ? SC : p.SEGS;
+        if constexpr (R == 1 && S == 1) {
+            // One tap: a step is MI*NI MFMAs, far too short to hide the two LDS round trips behind
+            // it (row table, then operands) when operands are asked for one step ahead -- counters
+            // and timings showed the MFMA waves of these layers waiting on LDS four fifths of the
+            // time.  Without a window no step depends on its neighbour, so: the KS waves take
+            // every KS-th (row pair, segment) step, whatever the row (rows per chunk need not be a
+            // multiple of 2*KS for all of them to work); operands are requested two steps ahead
+            // into a ring of three sets, the row table three steps ahead.
+            const int total = nrp * segs;
+            if (ks >= total) return;
+            const int n = (total - ks + KS - 1) / KS;
+            // step index of this wave's i-th step, clamped: requests past the end re-read the last step
+            auto entry_of = [&](int i) {
+                const int t = min(ks + i * KS, total - 1);
+                return lds16(tab + 32 * (int)fdiv(t, p.m_segs));
+            };
+            auto ask = [&](Ops &o, int i, const u32x4 &e) {
+                const int t = min(ks + i * KS, total - 1);
+                const int seg = t - (int)fdiv(t, p.m_segs) * segs;
+                const uint32_t rxx[R] = {xc + 2 * e[1]};
+                request(o, ac + 2 * e[0], rxx, seg, true);
+            };
+            Ops O0, O1, O2;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) O0.aw[mi].prev3 = O1.aw[mi].prev3 = O2.aw[mi].prev3 = 0;
+            u32x4 e0 = entry_of(0), e1 = entry_of(1), e_ahead = entry_of(2);
+            ask(O0, 0, e0);
+            ask(O1, 1, e1);
+            int i = 0;
+#define CAC_PW_PHASE(USE, GET)                    \
+    {                                             \
+        const u32x4 e_now = e_ahead;              \
+        e_ahead = entry_of(i + 3);                \
+        ask(GET, i + 2, e_now);                   \
+        mfma_step(USE);                           \
+        interleave();                             \
+        if (++i == n) break;                      \
+    }
+            for (;;) {
+                CAC_PW_PHASE(O0, O2)
+                CAC_PW_PHASE(O1, O0)
+                CAC_PW_PHASE(O2, O1)
+            }
+#undef CAC_PW_PHASE
+            return;
+        }
         const int nsteps = ((nrp - ks + KS - 1) / KS) * segs;
         if (KS > 1 && nsteps == 0) return;
 

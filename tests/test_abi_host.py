@@ -243,3 +243,19 @@ def test_auto_weight_gradient_picks_by_layer_size():
     assert B.dw_rk_executed_flops(d) * 4 == big.dw_flops
     assert B.cac_workspace_size(d, B.OP_BWD_WEIGHT_COMPRESSED) == \
         B.cac_workspace_size(B.desc_from_spec(big, dw_algo=B.DW_REDUCED_K), B.OP_BWD_WEIGHT_COMPRESSED)
+
+
+def test_probe_validates_before_launching():
+    """cac_probe: kind, pointers, size and iteration count are checked on the host."""
+    L = B.lib()
+    buf = ctypes.create_string_buffer(96)          # never dereferenced: every call below is refused
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 15) & ~15)
+    assert L.cac_probe(3, p, p, ctypes.c_size_t(1 << 20), 1, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(-1, p, p, ctypes.c_size_t(1 << 20), 1, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(B.PROBE_COPY, None, p, ctypes.c_size_t(1 << 20), 0, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(B.PROBE_COPY, p, None, ctypes.c_size_t(1 << 20), 0, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(B.PROBE_COPY, p, p, ctypes.c_size_t(8192), 0, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(B.PROBE_COPY, p, p, ctypes.c_size_t((1 << 20) + 8), 0, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(B.PROBE_MFMA, p, p, ctypes.c_size_t(1 << 20), -1, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(B.PROBE_MFMA, p, p, ctypes.c_size_t(1 << 20), (1 << 24) + 1, None) == B.ERR_INVALID_ARG
+    assert b"iters" in L.cac_last_error()

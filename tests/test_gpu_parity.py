@@ -334,3 +334,20 @@ def test_no_bias_and_empty_free_paths():
     t = synth.make_inputs(spec, "nobias")
     got = run_step(spec, t, has_bias=False)
     _check_step(spec, t, got, has_bias=False)
+
+
+def test_probe_kernels_run_and_the_copy_copies():
+    """The benchmark's yardstick kernels: the copy stream reproduces its source bit for bit and
+    leaves what lies beyond untouched; the read stream and the MFMA loop run to completion."""
+    import torch
+    from paper_2409_11902_amd import binding as B
+    n = (1 << 20) + 4096
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.full((n + 64,), 7, dtype=torch.uint8, device="cuda:0")
+    B.cac_probe(B.PROBE_COPY, src, dst, n)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and bool((dst[n:] == 7).all())
+    out = torch.zeros(8192, dtype=torch.uint8, device="cuda:0")
+    B.cac_probe(B.PROBE_READ, src, out, n)
+    B.cac_probe(B.PROBE_MFMA, src, out, n, iters=4)
+    torch.cuda.synchronize()
