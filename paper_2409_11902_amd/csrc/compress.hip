@@ -111,6 +111,15 @@ __device__ __forceinline__ void pool_and_store(const Geom &g, const float (&v)[K
         } else {
             Elem<T>::store(zrow + j0, res[0]);
         }
+    } else if (sizeof(T) == 2 && OPC >= 2 && g.Wp % 2 == 0) {
+        // a row of Z ends inside the last chunk (pooled rows of 14): every row still starts on a
+        // dword and the chunks on even elements, so pairs of neighbours leave as dword stores
+        if constexpr (sizeof(T) == 2 && OPC >= 2) {
+            uint32_t *dst = (uint32_t *)((bf16_t *)zrow + j0);
+#pragma unroll
+            for (int o = 0; o < OPC / 2; ++o)
+                if (j0 + 2 * o < g.Wp) dst[o] = (uint32_t)f32_to_bf16(res[2 * o]) | ((uint32_t)f32_to_bf16(res[2 * o + 1]) << 16);
+        }
     } else {
 #pragma unroll
         for (int o = 0; o < OPC; ++o)
