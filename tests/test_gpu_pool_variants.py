@@ -55,6 +55,8 @@ MAX_CASES = [
     (2, 6, 5, 9, 11, 3, 2, 1, 3, 3, synth.BF16),       # plain kernels
     (2, 4, 4, 10, 10, 1, 1, 0, 8, 8, synth.BF16),
     (2, 3, 3, 3, 3, 3, 1, 1, 4, 4, synth.BF16),        # tile larger than the map
+    (3, 50, 8, 14, 14, 3, 1, 1, 2, 2, synth.BF16),     # narrow rows: a thread per row pair, last wave not full
+    (2, 9, 8, 6, 10, 3, 1, 1, 2, 2, synth.BF16),
     (1, 1, 1, 1, 1, 1, 1, 0, 2, 2, synth.BF16),
     (3, 5, 6, 7, 9, 3, 1, 1, 2, 2, synth.F32),
     (2, 8, 4, 13, 16, 3, 1, 1, 4, 2, synth.F32),

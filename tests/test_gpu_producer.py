@@ -20,6 +20,9 @@ CASES = [
     (2, 4, 12, 20, 4, 2, synth.BF16), (2, 3, 5, 4, 2, 2, synth.BF16), (3, 4, 10, 10, 3, 3, synth.BF16), (2, 3, 9, 11, 1, 1, synth.BF16),
     (3, 5, 8, 8, 2, 2, synth.F32), (2, 7, 7, 9, 2, 2, synth.F32), (2, 4, 10, 7, 3, 2, synth.F32), (2, 3, 16, 12, 4, 4, synth.F32),
     (64, 64, 56, 56, 2, 2, synth.BF16), (128, 512, 7, 7, 2, 2, synth.BF16), (32, 256, 14, 14, 4, 4, synth.BF16),
+    # rows of 10, 12, 14 elements (a thread per row pair): fewer records than a wave, whole waves, whole waves and a rest, full size
+    (5, 3, 4, 12, 2, 2, synth.BF16), (16, 64, 14, 14, 2, 2, synth.BF16), (3, 50, 14, 14, 2, 2, synth.BF16), (2, 7, 6, 10, 2, 2, synth.BF16),
+    (256, 512, 14, 14, 2, 2, synth.BF16), (9, 33, 28, 28, 2, 2, synth.BF16),
 ]
 
 
