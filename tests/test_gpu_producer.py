@@ -78,7 +78,10 @@ def test_normalise_activate_compress(c):
     assert torch.equal(Xn3.view(torch.uint8), Xn.t.view(torch.uint8)) and torch.equal(Zn3.view(torch.uint8), Zn.t.view(torch.uint8))
 
 
-@pytest.mark.parametrize("c", CASES[:12] + [(16, 64, 28, 28, 2, 2, synth.BF16)], ids=[" ".join(map(str, c)) for c in CASES[:12]] + ["16 64 28 28 2 2 bf16"])
+BN_CASES = CASES[:12] + [(16, 64, 28, 28, 2, 2, synth.BF16), (64, 64, 56, 56, 2, 2, synth.BF16), (256, 512, 14, 14, 2, 2, synth.BF16)]
+
+
+@pytest.mark.parametrize("c", BN_CASES, ids=[" ".join(map(str, c)) for c in BN_CASES])
 def test_batch_norm_backward_from_the_compressed_record(c):
     from gpu_util import Guarded, download, upload
     N, C, H, W, kh, kw, dt = c
