@@ -254,6 +254,18 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
             kt[0] += 1
         r["prod_cold_ms"] = timed(torch, stream, prod_cold, 3 * ncopy, ncopy)
         B.cac_compress(L.d, L.X, L.Z, stream)   # (Z of the layer's own input again)
+        # batch normalisation's backward pass from the pooled record of its input (two launches),
+        # the incoming gradient rotating through the same buffers (it has the input's shape here)
+        stat = [torch.full((L.spec.C,), v, dtype=torch.float32, device="cuda:0") for v in (0.4, 1.3, 1.1)]
+        dg, dbt = torch.empty_like(stat[0]), torch.empty_like(stat[0])
+        bt = [0]
+        nb = B.cac_workspace_size(L.d, B.OP_BN_BWD)
+        wsb = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda:0")
+
+        def bn_cold():
+            B.cac_bn_bwd_compressed(L.d, L.Z, xs[bt[0] % ncopy], stat[0], stat[1], stat[2], dg, dbt, Xn, wsb, stream)
+            bt[0] += 1
+        r["bn_bwd_cold_ms"] = timed(torch, stream, bn_cold, 3 * ncopy, ncopy)
         del xs, Xn
         r["cos"] = grad_cosine(L, B, synth, torch, stream) if L.spec.dtype == synth.BF16 else (None, None)
         rows.append(r)
@@ -282,6 +294,9 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
              # normalise + activate + pool fused at the producer: reads X once, writes X' and Z
              "producer_fused_cold_us": round(r["prod_cold_ms"] * 1e3, 2),
              "producer_fused_cold_gbps": round((2 * L.x_bytes + L.z_bytes) / (r["prod_cold_ms"] * 1e-3) / 1e9, 1),
+             # batch normalisation's backward pass from the pooled record: reads dY twice and Z twice, writes dX
+             "bn_bwd_compressed_cold_us": round(r["bn_bwd_cold_ms"] * 1e3, 2),
+             "bn_bwd_compressed_cold_gbps": round((3 * L.x_bytes + 2 * L.z_bytes) / (r["bn_bwd_cold_ms"] * 1e-3) / 1e9, 1),
              "x_bytes": L.x_bytes, "z_bytes": L.z_bytes, "saved_ratio": round(L.x_bytes / L.z_bytes, 3)}
         if rk:
             # the reduced-K form executes fewer multiply-adds for the same result: nominal flops

@@ -48,7 +48,7 @@
 extern "C" {
 #endif
 
-#define CAC_VERSION 301 /* major*10000 + minor*100 + patch */
+#define CAC_VERSION 302 /* major*10000 + minor*100 + patch */
 
 typedef enum cac_status {
     CAC_OK = 0,
@@ -105,7 +105,8 @@ typedef enum cac_op {
     CAC_OP_COMPRESS = 3,
     CAC_OP_BWD_BIAS = 4,
     CAC_OP_GRAD_COSINE = 5,
-    CAC_OP_BWD_WEIGHT_AND_DATA = 6
+    CAC_OP_BWD_WEIGHT_AND_DATA = 6,
+    CAC_OP_BN_BWD = 7
 } cac_op;
 
 /* One convolution layer with a compressed saved input.  Plain data, filled by
@@ -235,9 +236,11 @@ int cac_bn_relu_fwd_compress(const cac_desc *d, const void *Y, const float *scal
  *   dX        = gamma[c] * invstd[c] * (dY - dbeta[c] / M - xhat~ * dgamma[c] / M)
  * i.e. the exact formulas with the saved activation replaced by its inflated record; dbeta is
  * exact.  mean, invstd, gamma: float [C_in], read; dgamma, dbeta: float [C_in], written; dX
- * [N][C_in][H][W] in the tensors' type, written.  Sums are taken in a fixed order. */
+ * [N][C_in][H][W] in the tensors' type, written.  Sums are taken in a fixed order.
+ * ws: cac_workspace_size(d, CAC_OP_BN_BWD) bytes (partial sums of the channels' slices; 0 for many
+ * channels or plain kernels). */
 int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, const float *mean, const float *invstd,
-                          const float *gamma, float *dgamma, float *dbeta, void *dX, void *stream);
+                          const float *gamma, float *dgamma, float *dbeta, void *dX, void *ws, size_t ws_bytes, void *stream);
 
 /* Yardsticks for benchmarks (no part of the method): what this machine attains on a bare
  * matrix-core loop and on a bare stream, to set a kernel's rate against.

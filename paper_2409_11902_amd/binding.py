@@ -23,7 +23,7 @@ DW_INFLATE, DW_REDUCED_K, DW_AUTO = 0, 1, 2
 EDGE_CEIL_VALID, EDGE_FLOOR_DROP = 0, 1
 POOL_MEAN, POOL_MAX = 0, 1
 (OP_FWD_AND_COMPRESS, OP_BWD_WEIGHT_COMPRESSED, OP_BWD_DATA, OP_COMPRESS, OP_BWD_BIAS, OP_GRAD_COSINE,
- OP_BWD_WEIGHT_AND_DATA) = range(7)
+ OP_BWD_WEIGHT_AND_DATA, OP_BN_BWD) = range(8)
 
 EXPORTS = (
     "cac_version", "cac_last_error", "cac_out_shape", "cac_pooled_shape", "cac_workspace_size", "cac_describe_plan",
@@ -81,7 +81,7 @@ def lib() -> ctypes.CDLL:
         L.conv_bwd_bias.argtypes = [dp, vp, vp, vp]
         L.cac_probe.argtypes = [ctypes.c_int, vp, vp, sz, ctypes.c_int, vp]
         L.cac_bn_relu_fwd_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
-        L.cac_bn_bwd_compressed.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.cac_bn_bwd_compressed.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cac_grad_cosine.argtypes = [dp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         for n in EXPORTS[2:]:
             getattr(L, n).restype = ctypes.c_int
@@ -198,9 +198,10 @@ def cac_bn_relu_fwd_compress(d, Y, scale, shift, X_next, Z_next, Z_in=None, stre
                                           _ptr(Z_in), _stream(stream)))
 
 
-def cac_bn_bwd_compressed(d, Z_in, dY, mean, invstd, gamma, dgamma, dbeta, dX, stream=None):
+def cac_bn_bwd_compressed(d, Z_in, dY, mean, invstd, gamma, dgamma, dbeta, dX, ws=None, stream=None):
+    wp, wb = _ws(ws)
     _check(lib().cac_bn_bwd_compressed(ctypes.byref(d), _ptr(Z_in), _ptr(dY), _ptr(mean), _ptr(invstd), _ptr(gamma),
-                                       _ptr(dgamma), _ptr(dbeta), _ptr(dX), _stream(stream)))
+                                       _ptr(dgamma), _ptr(dbeta), _ptr(dX), wp, wb, _stream(stream)))
 
 
 def cac_probe(kind, src, dst, nbytes, iters=0, stream=None):

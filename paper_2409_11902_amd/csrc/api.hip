@@ -147,6 +147,7 @@ static size_t workspace_bytes(const Geom &g, int dtype, int op)
     // both gradients in one call: the partial sums are still being read when the repacks are written
     if (op == CAC_OP_BWD_WEIGHT_AND_DATA)
         return both_dw_bytes(g, dtype) + workspace_bytes(g, dtype, CAC_OP_BWD_DATA);
+    if (op == CAC_OP_BN_BWD) return bn_bwd_workspace_bytes(g, dtype);
     return 0;
 }
 
@@ -255,7 +256,7 @@ int cac_workspace_size(const cac_desc *d, int op, size_t *bytes)
     Geom g;
     int rc = make_geom(d, &g, true);
     if (rc) return rc;
-    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_WEIGHT_AND_DATA) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BN_BWD) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     if (!bytes) return fail(CAC_ERR_INVALID_ARG, "bytes is NULL");
     *bytes = workspace_bytes(g, d->dtype, op);
     return CAC_OK;
@@ -281,7 +282,7 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
     int rc = make_geom(d, &g, true);
     if (rc) return rc;
     if (!buf || buf_len == 0) return fail(CAC_ERR_INVALID_ARG, "buf is NULL or empty");
-    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BWD_WEIGHT_AND_DATA) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
+    if (op < CAC_OP_FWD_AND_COMPRESS || op > CAC_OP_BN_BWD) return fail(CAC_ERR_INVALID_ARG, "unknown op %d", op);
     DwMfmaPlan plan;
     DwRkPlan rk;
     if (op == CAC_OP_BWD_WEIGHT_COMPRESSED && reduced_k_plan(g, d->dtype, &rk)) {
@@ -307,6 +308,10 @@ int cac_describe_plan(const cac_desc *d, int op, char *buf, size_t buf_len)
                describe_conv_mfma(g, d->dtype, op == CAC_OP_BWD_DATA, buf, buf_len)) {
     } else if (op == CAC_OP_COMPRESS || op == CAC_OP_GRAD_COSINE) {
         snprintf(buf, buf_len, "streaming kernel");
+    } else if (op == CAC_OP_BN_BWD) {
+        const size_t n = bn_bwd_workspace_bytes(g, d->dtype);
+        snprintf(buf, buf_len, "sums and element-wise pass (%zu slices per channel where the chunk kernels take the tile)",
+                 n ? n / (2 * sizeof(float) * (size_t)g.C) : (size_t)1);
     } else if (op == CAC_OP_BWD_WEIGHT_AND_DATA) {
         char dx[64];
         const bool split = (reduced_k_plan(g, d->dtype, &rk)) ? !rk.p.direct
@@ -433,7 +438,7 @@ int cac_bn_relu_fwd_compress(const cac_desc *d, const void *Y, const float *scal
 }
 
 int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, const float *mean, const float *invstd,
-                          const float *gamma, float *dgamma, float *dbeta, void *dX, void *stream)
+                          const float *gamma, float *dgamma, float *dbeta, void *dX, void *ws, size_t ws_bytes, void *stream)
 {
     Geom g;
     int rc = make_geom(d, &g, true);
@@ -442,6 +447,10 @@ int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, c
         (rc = check_ptr(invstd, "invstd")) || (rc = check_ptr(gamma, "gamma")) || (rc = check_ptr(dgamma, "dgamma")) ||
         (rc = check_ptr(dbeta, "dbeta")) || (rc = check_ptr(dX, "dX")))
         return rc;
+    if ((rc = check_ws(g, d->dtype, CAC_OP_BN_BWD, ws, ws_bytes, nullptr))) return rc;
+    hipError_t e = hipSuccess;
+    if (launch_bn_bwd_fast(g, d->dtype, Z_in, dY, mean, invstd, gamma, dgamma, dbeta, dX, ws, (hipStream_t)stream, &e))
+        return launched(e, "batch normalisation backward");
     if ((long)g.N * g.C > 65535L * 32767L) return fail(CAC_ERR_UNSUPPORTED, "N * C_in too large for this kernel's grid");
     return launched(launch_bn_bwd(g, d->dtype, Z_in, dY, mean, invstd, gamma, dgamma, dbeta, dX, (hipStream_t)stream),
                     "batch normalisation backward");

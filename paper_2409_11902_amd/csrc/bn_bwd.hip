@@ -1,0 +1,231 @@
+// Batch normalisation's backward pass from the pooled record of its input (the paper's conclusion
+// names compressing what batch normalisation saves as a next step; the formulas are the textbook
+// ones with the saved input replaced by its inflated record):
+//   xhat~ = (Zin[n,c,h/kh,w/kw] - mean[c]) * invstd[c],  M = N*H*W
+//   dbeta[c] = sum dy      dgamma[c] = sum dy * xhat~
+//   dx = gamma[c] * invstd[c] * (dy - dbeta[c] / M - xhat~ * dgamma[c] / M)
+// Bandwidth-bound, gfx950.  Three launches over the chunks of compress.hip (16 bytes of kh rows
+// of dY and the pooled values under them, so that a pooled value is read once per tile):
+//   1. partial sums: a block per (channel, slice of the channel's chunks over all images); a
+//      channel is shared out over as many slices as it takes to have about 2048 blocks;
+//   2. the slices of a channel added in a fixed order (skipped when a channel is one slice);
+//   3. the element-wise pass, one thread per chunk, 16-byte stores.
+// Everything is summed in an order that depends on the shape only: results are reproducible.
+#include "chunk.h"
+
+namespace cac {
+
+namespace {
+
+constexpr int kT = 256;
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+struct BnPlan {
+    int cpr;               // chunks per row
+    uint32_t ipp;          // chunks per plane (pooled rows x chunks per row)
+    uint32_t per_channel;  // chunks of a channel: N * ipp
+    uint32_t per_slice;    // chunks a block of the first launch goes through
+    int S;                 // slices per channel
+    uint32_t total;        // chunks of the tensor
+    double inv_cpr, inv_ipp, inv_hp, inv_c;
+};
+
+// The chunk's dY values (rows past the plane read as zero) and what the pooled values under it say
+// about the normalised input: xh[o] = (Z - mean) * invstd, 0 where the pooled column does not exist.
+template <typename T, int EPC, int KH, int KW>
+__device__ __forceinline__ void load_chunk(const Geom &g, rsrc_t rs_dy, const T *__restrict__ Zin, uint32_t plane, int i, int ch, float mu,
+                                           float is, float (&v)[KH][EPC], float (&xh)[EPC / KW], int &rows)
+{
+    constexpr int OPC = EPC / KW;
+    const int h0 = i * KH;
+    rows = min(KH, g.H - h0);
+#pragma unroll
+    for (int a = 0; a < KH; ++a)
+        Chunk<T, EPC>::load(rs_dy, (plane * g.H + h0 + a) * g.W + ch * EPC, a < rows, g.W & 1, v[a]);
+    const T *z = Zin + ((long)plane * g.Hp + i) * g.Wp + ch * OPC;
+#pragma unroll
+    for (int o = 0; o < OPC; ++o) xh[o] = ch * OPC + o < g.Wp ? (Elem<T>::load(z + o) - mu) * is : 0.f;
+}
+
+template <typename T, int EPC, int KH, int KW>
+__global__ void __launch_bounds__(kT) bn_partial_kernel(Geom g, BnPlan q, const T *__restrict__ Zin, const T *__restrict__ dY,
+                                                        const float *__restrict__ mean, const float *__restrict__ invstd,
+                                                        float *__restrict__ o_dy, float *__restrict__ o_dx)
+{
+    constexpr int OPC = EPC / KW;
+    __shared__ float red[2][kT / 64];
+    const int c = blockIdx.x / q.S, s = blockIdx.x - c * q.S;
+    const float mu = mean[c], is = invstd[c];
+    const rsrc_t rs = make_rsrc(dY, (uint32_t)g.N * g.C * g.H * g.W * (uint32_t)sizeof(T));
+    const uint32_t end = min((uint32_t)(s + 1) * q.per_slice, q.per_channel);
+    float sdy = 0.f, sdx = 0.f;
+    for (uint32_t it = (uint32_t)s * q.per_slice + threadIdx.x; it < end; it += kT) {
+        const uint32_t n = udiv(it, q.inv_ipp), rem = it - n * q.ipp;
+        const uint32_t i = udiv(rem, q.inv_cpr), ch = rem - i * q.cpr;
+        float v[KH][EPC], xh[OPC];
+        int rows;
+        load_chunk<T, EPC, KH, KW>(g, rs, Zin, n * g.C + c, (int)i, (int)ch, mu, is, v, xh, rows);
+        const int left = g.W - (int)ch * EPC; // columns of the chunk inside the row
+#pragma unroll
+        for (int o = 0; o < OPC; ++o) {
+            float t = 0.f; // the tile's dY, row by row (rows past the plane are zeros already)
+#pragma unroll
+            for (int a = 0; a < KH; ++a)
+#pragma unroll
+                for (int b = 0; b < KW; ++b)
+                    if (o * KW + b < left) t += v[a][o * KW + b];
+            sdy += t;
+            sdx += t * xh[o];
+        }
+    }
+    sdy = wave_sum(sdy);
+    sdx = wave_sum(sdx);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) {
+        red[0][wave] = sdy;
+        red[1][wave] = sdx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        o_dy[blockIdx.x] = ((red[0][0] + red[0][1]) + red[0][2]) + red[0][3];
+        o_dx[blockIdx.x] = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];
+    }
+}
+
+// One wave per channel: its S <= 64 slices, one per lane, added by the wave's fixed tree.
+__global__ void __launch_bounds__(64) bn_finish_kernel(int S, const float *__restrict__ p_dy, const float *__restrict__ p_dx,
+                                                       float *__restrict__ dgamma, float *__restrict__ dbeta)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    const float a = lane < S ? p_dy[c * S + lane] : 0.f, b = lane < S ? p_dx[c * S + lane] : 0.f;
+    const float sa = wave_sum(a), sb = wave_sum(b);
+    if (lane == 0) {
+        dbeta[c] = sa;
+        dgamma[c] = sb;
+    }
+}
+
+template <typename T, int EPC, int KH, int KW>
+__global__ void __launch_bounds__(kT) bn_dx_kernel(Geom g, BnPlan q, const T *__restrict__ Zin, const T *__restrict__ dY,
+                                                   const float *__restrict__ mean, const float *__restrict__ invstd,
+                                                   const float *__restrict__ gamma, const float *__restrict__ dgamma,
+                                                   const float *__restrict__ dbeta, T *__restrict__ dX)
+{
+    constexpr int OPC = EPC / KW;
+    const uint32_t idx = blockIdx.x * (uint32_t)kT + threadIdx.x;
+    if (idx >= q.total) return;
+    const uint32_t rowi = udiv(idx, q.inv_cpr), ch = idx - rowi * q.cpr;
+    const uint32_t plane = udiv(rowi, q.inv_hp), i = rowi - plane * g.Hp;
+    const uint32_t c = plane - udiv(plane, q.inv_c) * (uint32_t)g.C;
+    const float inv_m = 1.0f / ((float)g.N * (float)(g.H * g.W));
+    const float mu = mean[c], is = invstd[c], k = gamma[c] * is;
+    const float mdy = dbeta[c] * inv_m, mdx = dgamma[c] * inv_m;
+    const rsrc_t rs = make_rsrc(dY, (uint32_t)g.N * g.C * g.H * g.W * (uint32_t)sizeof(T));
+    float v[KH][EPC], xh[OPC];
+    int rows;
+    load_chunk<T, EPC, KH, KW>(g, rs, Zin, plane, (int)i, (int)ch, mu, is, v, xh, rows);
+    const int w0 = (int)ch * EPC, left = g.W - w0;
+#pragma unroll
+    for (int a = 0; a < KH; ++a) {
+        if (a >= rows) continue;
+        float out[EPC];
+#pragma unroll
+        for (int b = 0; b < EPC; ++b) out[b] = k * (v[a][b] - mdy - xh[b / KW] * mdx);
+        store_chunk<T, EPC>(dX, ((long)plane * g.H + (int)i * KH + a) * g.W + w0, left, out);
+    }
+}
+
+inline unsigned cdiv(long a, long b) { return (unsigned)((a + b - 1) / b); }
+
+template <int EPC> bool make_plan(const Geom &g, BnPlan *q)
+{
+    q->cpr = (g.W + EPC - 1) / EPC;
+    const long ipp = (long)g.Hp * q->cpr, per_channel = (long)g.N * ipp, total = per_channel * g.C;
+    if (total >= (1L << 31) || q->cpr >= (1 << 16) || ipp >= (1 << 16) || g.Hp >= (1 << 16) || g.C >= (1 << 16)) return false; // udiv's range
+    q->ipp = (uint32_t)ipp;
+    q->per_channel = (uint32_t)per_channel;
+    q->total = (uint32_t)total;
+    int S = (int)std::max(1L, std::min(64L, 2048L / g.C));
+    S = (int)std::max(1L, std::min((long)S, (per_channel + kT - 1) / kT)); // no slice without a chunk per thread
+    q->per_slice = (uint32_t)((per_channel + S - 1) / S);
+    q->S = (int)((per_channel + q->per_slice - 1) / q->per_slice);
+    q->inv_cpr = 1.0 / q->cpr;
+    q->inv_ipp = 1.0 / (double)ipp;
+    q->inv_hp = 1.0 / g.Hp;
+    q->inv_c = 1.0 / g.C;
+    return true;
+}
+
+// false: a pooling tile the chunk kernels do not take
+template <typename T, int EPC>
+bool launch_t(const Geom &g, const BnPlan &q, const void *Zin, const void *dY, const float *mean, const float *invstd, const float *gamma,
+              float *dgamma, float *dbeta, void *dX, float *ws, hipStream_t st)
+{
+    const bool one = q.S == 1; // a channel is one slice: the first launch writes the sums themselves
+    float *o_dy = one ? dbeta : ws, *o_dx = one ? dgamma : ws + (size_t)g.C * q.S;
+#define CAC_BN(KH, KW)                                                                                                              \
+    {                                                                                                                               \
+        hipLaunchKernelGGL((bn_partial_kernel<T, EPC, KH, KW>), dim3((unsigned)(g.C * q.S)), dim3(kT), 0, st, g, q, (const T *)Zin,  \
+                           (const T *)dY, mean, invstd, o_dy, o_dx);                                                                \
+        if (!one) hipLaunchKernelGGL(bn_finish_kernel, dim3((unsigned)g.C), dim3(64), 0, st, q.S, o_dy, o_dx, dgamma, dbeta);       \
+        hipLaunchKernelGGL((bn_dx_kernel<T, EPC, KH, KW>), dim3(cdiv(q.total, kT)), dim3(kT), 0, st, g, q, (const T *)Zin,           \
+                           (const T *)dY, mean, invstd, gamma, dgamma, dbeta, (T *)dX);                                             \
+        return true;                                                                                                                \
+    }
+    if (g.kh == 2 && g.kw == 2) CAC_BN(2, 2)
+    if (g.kh == 4 && g.kw == 4) CAC_BN(4, 4)
+    if (g.kh == 1 && g.kw == 1) CAC_BN(1, 1)
+    if (g.kh == 2 && g.kw == 4) CAC_BN(2, 4)
+    if (g.kh == 4 && g.kw == 2) CAC_BN(4, 2)
+#undef CAC_BN
+    return false;
+}
+
+// The chunk width for a geometry (0: no chunk kernel) and its plan.
+int plan_of(const Geom &g, int dtype, BnPlan *q)
+{
+    if ((long)g.N * g.C * g.H * g.W * 4 >= (1L << 31)) return 0; // 32-bit buffer offsets
+    const bool tile_ok = (g.kh == g.kw && (g.kh == 1 || g.kh == 2 || g.kh == 4)) || (g.kh == 2 && g.kw == 4) || (g.kh == 4 && g.kw == 2);
+    if (!tile_ok) return 0;
+    const int epc = dtype == CAC_F32 ? 4 : (g.W >= 8 ? 8 : 4);
+    if (g.kw > epc) return 0;
+    const bool ok = epc == 8 ? make_plan<8>(g, q) : make_plan<4>(g, q);
+    return ok ? epc : 0;
+}
+
+} // namespace
+
+// Bytes of device scratch launch_bn_bwd_fast needs (the slices' partial sums); 0 when a channel is
+// one slice or the geometry runs on the plain kernels.
+size_t bn_bwd_workspace_bytes(const Geom &g, int dtype)
+{
+    BnPlan q;
+    if (!plan_of(g, dtype, &q) || q.S == 1) return 0;
+    return (size_t)2 * g.C * q.S * sizeof(float);
+}
+
+// True when the chunk kernels cover the geometry (and have been launched).
+bool launch_bn_bwd_fast(const Geom &g, int dtype, const void *Zin, const void *dY, const float *mean, const float *invstd,
+                        const float *gamma, float *dgamma, float *dbeta, void *dX, void *ws, hipStream_t st, hipError_t *err)
+{
+    BnPlan q;
+    const int epc = plan_of(g, dtype, &q);
+    if (!epc) return false;
+    bool ok;
+    if (dtype == CAC_F32)
+        ok = launch_t<float, 4>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);
+    else if (epc == 8)
+        ok = launch_t<bf16_t, 8>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);
+    else
+        ok = launch_t<bf16_t, 4>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);
+    if (ok) *err = hipGetLastError();
+    return ok;
+}
+
+} // namespace cac

@@ -10,60 +10,12 @@
 // a row are handed to consecutive threads, so a wave reads whole rows.
 // Ragged edges follow the ceil/valid rule: a tile that sticks out is averaged
 // over the elements it really has.
-#include "common.h"
+#include "chunk.h"
 #include <type_traits>
 
 namespace cac {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-constexpr uint32_t kNoLoad = 0x80000000u;
-
-// EPC consecutive elements starting at element e (any alignment the type
-// allows) as floats; elements past the tensor read as zero.
-template <typename T, int EPC> struct Chunk;
-template <int EPC> struct Chunk<bf16_t, EPC> {
-    static_assert(EPC == 8 || EPC == 4, "");
-    // odd: rows can start on odd elements (odd W); only then the extra dword is fetched
-    static __device__ __forceinline__ void load(rsrc_t rs, uint32_t e, bool live, bool odd, float (&out)[EPC])
-    {
-        // dword-aligned address at or below the element; an odd start is shifted out afterwards
-        const uint32_t byte = live ? (e & ~1u) * 2u : kNoLoad;
-        uint32_t d[EPC / 2 + 1];
-        d[EPC / 2] = 0;
-        if constexpr (EPC == 8) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, byte, 0, 0);
-            d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
-            if (odd) d[4] = __builtin_amdgcn_raw_buffer_load_b32(rs, byte == kNoLoad ? kNoLoad : byte + 16, 0, 0);
-        } else {
-            typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, byte, 0, 0);
-            d[0] = v[0]; d[1] = v[1];
-            if (odd) d[2] = __builtin_amdgcn_raw_buffer_load_b32(rs, byte == kNoLoad ? kNoLoad : byte + 8, 0, 0);
-        }
-        const uint32_t sh = (e & 1u) * 16u;
-#pragma unroll
-        for (int j = 0; j < EPC / 2; ++j) {
-            const uint32_t w = __builtin_amdgcn_alignbit(d[j + 1], d[j], sh);
-            out[2 * j] = __uint_as_float(w << 16);
-            out[2 * j + 1] = __uint_as_float(w & 0xffff0000u);
-        }
-    }
-};
-template <> struct Chunk<float, 4> {
-    static __device__ __forceinline__ void load(rsrc_t rs, uint32_t e, bool live, bool, float (&out)[4])
-    {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, live ? e * 4u : kNoLoad, 0, 0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) out[j] = __uint_as_float(v[j]);
-    }
-};
-
-// floor(x / d) for x < 2^31 and d < 2^16, given inv = 1.0 / d: the quotient's
-// fractional part is a multiple of 1/d >= 2^-16, so adding 2^-18 before
-// truncating absorbs the rounding of x * inv without ever reaching the next integer.
-__device__ __forceinline__ uint32_t udiv(uint32_t x, double inv) { return (uint32_t)((double)x * inv + 0x1p-18); }
 
 // What the producer form of the kernel does on top of compression (see launch_producer_fast).
 struct Producer {

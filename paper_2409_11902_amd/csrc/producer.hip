@@ -15,8 +15,9 @@
 // channel, with x replaced by the inflated record (x~ = Zin repeated over its tiles):
 //   dbeta[c]  = sum dy            dgamma[c] = sum dy * xhat~
 //   dx        = gamma * invstd * (dy - dbeta / M - xhat~ * dgamma / M)
-// Two launches: per-channel sums in a fixed order (one block per channel), then the element-wise
-// pass.  The sums are exact in the same sense as the weight gradient: only xhat~ is approximate.
+// Here: the plain form for pooling tiles the chunk kernels of bn_bwd.hip do not take -- two launches,
+// per-channel sums in a fixed order (one block per channel), then the element-wise pass.  The sums
+// are exact in the same sense as the weight gradient: only xhat~ is approximate.
 #include "common.h"
 
 namespace cac {

@@ -114,7 +114,7 @@ static void abi_cases()
                                 if (cac_out_shape(&d, &P, &Q) != CAC_OK) continue;
                                 CHECK(cac_pooled_shape(&d, &Hp, &Wp, &zb, &xb) == CAC_OK);
                                 CHECK(zb <= xb || k == 1);
-                                for (int op = CAC_OP_FWD_AND_COMPRESS; op <= CAC_OP_BWD_WEIGHT_AND_DATA; ++op) {
+                                for (int op = CAC_OP_FWD_AND_COMPRESS; op <= CAC_OP_BN_BWD; ++op) {
                                     CHECK(cac_workspace_size(&d, op, &ws) == CAC_OK);
                                     CHECK(cac_describe_plan(&d, op, buf, sizeof buf) == CAC_OK);
                                     CHECK(strlen(buf) < sizeof buf);

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert B.cac_version() == 301
+    assert B.cac_version() == 302
 
 
 def test_desc_layout_matches_header():
@@ -259,3 +259,23 @@ def test_probe_validates_before_launching():
     assert L.cac_probe(B.PROBE_MFMA, p, p, ctypes.c_size_t(1 << 20), -1, None) == B.ERR_INVALID_ARG
     assert L.cac_probe(B.PROBE_MFMA, p, p, ctypes.c_size_t(1 << 20), (1 << 24) + 1, None) == B.ERR_INVALID_ARG
     assert b"iters" in L.cac_last_error()
+
+
+def test_bn_backward_workspace_and_validation():
+    """Few channels are shared out over slices (partial sums in the workspace), many are not; the
+    call refuses a missing workspace before launching anything."""
+    few = B.make_desc(64, 64, 8, 56, 56, 1, 1, 1, 1, 0, 0, 2, 2)
+    many = B.make_desc(8, 4096, 8, 14, 14, 1, 1, 1, 1, 0, 0, 2, 2)
+    odd_tile = B.make_desc(8, 64, 8, 15, 15, 1, 1, 1, 1, 0, 0, 3, 3)
+    n = B.cac_workspace_size(few, B.OP_BN_BWD)
+    assert n == 2 * 64 * 32 * 4                      # 2048 blocks / 64 channels = 32 slices, two sums each
+    assert B.cac_workspace_size(many, B.OP_BN_BWD) == 0 and B.cac_workspace_size(odd_tile, B.OP_BN_BWD) == 0
+    buf = ctypes.create_string_buffer(96)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 15) & ~15)
+    L = B.lib()
+    rc = L.cac_bn_bwd_compressed(ctypes.byref(few), p, p, p, p, p, p, p, p, None, 0, None)
+    assert rc == B.ERR_WORKSPACE_TOO_SMALL
+    rc = L.cac_bn_bwd_compressed(ctypes.byref(few), p, p, p, p, p, p, p, p, p, n - 16, None)
+    assert rc == B.ERR_WORKSPACE_TOO_SMALL
+    rc = L.cac_bn_bwd_compressed(ctypes.byref(few), p, None, p, p, p, p, p, p, p, n, None)
+    assert rc == B.ERR_INVALID_ARG

@@ -96,7 +96,8 @@ def test_batch_norm_backward_from_the_compressed_record(c):
     B.cac_compress(d, Yd, Zin)
     dg, db, dX = Guarded((C,), torch.float32), Guarded((C,), torch.float32), Guarded((N, C, H, W), td)
     f = lambda a: torch.from_numpy(a).cuda()
-    B.cac_bn_bwd_compressed(d, Zin, dYd, f(mean), f(invstd), f(gamma), dg.t, db.t, dX.t)
+    from gpu_util import workspace
+    B.cac_bn_bwd_compressed(d, Zin, dYd, f(mean), f(invstd), f(gamma), dg.t, db.t, dX.t, workspace(d, B.OP_BN_BWD))
     torch.cuda.synchronize()
     for b in (dg, db, dX):
         b.check("bn backward")
