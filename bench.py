@@ -233,6 +233,9 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
         r["fwd_ms"] = timed(torch, stream, lambda: B.conv_fwd_and_compress(L.d, L.X, L.W, L.b, L.Y, L.Z, L.ws[B.OP_FWD_AND_COMPRESS],
                                                                         stream), 30, 5)
         r["dx_ms"] = timed(torch, stream, lambda: B.conv_bwd_data(L.d, L.W, L.dY, L.dX, L.ws[B.OP_BWD_DATA], stream), 30, 5)
+        # the bias gradient (one read of dY)
+        dbv = torch.empty((L.spec.K,), dtype=torch.float32, device="cuda:0")
+        r["db_ms"] = timed(torch, stream, lambda: B.conv_bwd_bias(L.d, L.dY, dbv, stream), 50, 5)
         # compress alone: warm (same buffers) and cold (rotating)
         r["cmp_warm_ms"] = timed(torch, stream, lambda: B.cac_compress(L.d, L.X, L.Z, stream), 50, 5)
         ncopy = int(min(48, max(2, COLD_BYTES // max(L.x_bytes, 1) + 1)))
@@ -289,6 +292,7 @@ def measure_workload(name, specs, args, B, synth, torch, np, detailed):
              "dw_roof_us": round(L.dw_tmin_us, 2), "dw_frac_of_binding_roof": round(frac_roof, 4),
              "dw_frac_of_mfma_peak": round(dw_tf / L.peak_tflops, 4),
              "fwd_compress_us": round(r["fwd_ms"] * 1e3, 2), "dx_us": round(r["dx_ms"] * 1e3, 2),
+             "db_us": round(r["db_ms"] * 1e3, 2), "db_gbps": round(L.dy_bytes / (r["db_ms"] * 1e-3) / 1e9, 1),
              "compress_cold_gbps": round(cg, 1), "compress_warm_gbps": round(wg, 1), "compress_bytes": L.bytes["compress"],
              "compress_cold_us": round(r["cmp_cold_ms"] * 1e3, 2),
              # normalise + activate + pool fused at the producer: reads X once, writes X' and Z

@@ -472,6 +472,8 @@ int conv_bwd_bias(const cac_desc *d, const void *dY, void *db, void *stream)
     int rc = make_geom(d, &g, true);
     if (rc) return rc;
     if ((rc = check_ptr(dY, "dY")) || (rc = check_ptr(db, "db"))) return rc;
+    hipError_t e = hipSuccess;
+    if (launch_db_fast(g, d->dtype, dY, (float *)db, (hipStream_t)stream, &e)) return launched(e, "bias gradient");
     return launched(launch_db(g, d->dtype, dY, (float *)db, (hipStream_t)stream), "bias gradient");
 }
 

@@ -11,6 +11,7 @@
 //   2. the slices of a channel added in a fixed order (skipped when a channel is one slice);
 //   3. the element-wise pass, one thread per chunk, 16-byte stores.
 // Everything is summed in an order that depends on the shape only: results are reproducible.
+// Also here, for the helpers it shares: the bias gradient db = sum of dY over n, p, q (db_kernel).
 #include "chunk.h"
 
 namespace cac {
@@ -141,6 +142,44 @@ __global__ void __launch_bounds__(kT) bn_dx_kernel(Geom g, BnPlan q, const T *__
     }
 }
 
+// db[o] = sum over n, p, q of dY[n,o,p,q] (bias-gradient formula of the compression figure): a block of
+// 1024 threads per output channel streams the channel's N planes (each a contiguous run) in 16-byte
+// chunks, two in flight per thread; fixed order, no scratch.
+template <typename T, int EPC>
+__global__ void __launch_bounds__(1024) db_kernel(int N, int K, int pq, uint32_t cpp, double inv_cpp, const T *__restrict__ dY,
+                                                  float *__restrict__ db)
+{
+    __shared__ float red[16];
+    const int o = blockIdx.x;
+    const rsrc_t rs = make_rsrc(dY, (uint32_t)N * K * pq * (uint32_t)sizeof(T));
+    const uint32_t total = (uint32_t)N * cpp;
+    auto chunk = [&](uint32_t it, float (&v)[EPC], int &left) {
+        const uint32_t n = udiv(min(it, total - 1), inv_cpp), ch = min(it, total - 1) - n * cpp;
+        Chunk<T, EPC>::load(rs, (n * K + o) * pq + ch * EPC, it < total, pq & 1, v);
+        left = pq - (int)ch * EPC;
+    };
+    float acc = 0.f;
+    for (uint32_t it = threadIdx.x; it < total; it += 2048) {
+        float v0[EPC], v1[EPC];
+        int l0, l1;
+        chunk(it, v0, l0);
+        chunk(it + 1024, v1, l1);
+#pragma unroll
+        for (int b = 0; b < EPC; ++b) acc += b < l0 ? v0[b] : 0.f;
+#pragma unroll
+        for (int b = 0; b < EPC; ++b) acc += b < l1 ? v1[b] : 0.f; // (a chunk past the end was not loaded: zeros)
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += red[w];
+        db[o] = t;
+    }
+}
+
 inline unsigned cdiv(long a, long b) { return (unsigned)((a + b - 1) / b); }
 
 template <int EPC> bool make_plan(const Geom &g, BnPlan *q)
@@ -226,6 +265,24 @@ bool launch_bn_bwd_fast(const Geom &g, int dtype, const void *Zin, const void *d
         ok = launch_t<bf16_t, 4>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);
     if (ok) *err = hipGetLastError();
     return ok;
+}
+
+// True when the streaming kernel takes the shape (and has been launched).
+bool launch_db_fast(const Geom &g, int dtype, const void *dY, float *db, hipStream_t st, hipError_t *err)
+{
+    const long pq = (long)g.P * g.Q;
+    if ((long)g.N * g.K * pq * 4 >= (1L << 31)) return false; // 32-bit buffer offsets
+    const int epc = dtype == CAC_F32 ? 4 : 8;
+    const long cpp = (pq + epc - 1) / epc;
+    if (cpp >= (1 << 16) || (long)g.N * cpp >= (1L << 31)) return false; // udiv's range
+    if (dtype == CAC_F32)
+        hipLaunchKernelGGL((db_kernel<float, 4>), dim3((unsigned)g.K), dim3(1024), 0, st, g.N, g.K, (int)pq, (uint32_t)cpp, 1.0 / (double)cpp,
+                           (const float *)dY, db);
+    else
+        hipLaunchKernelGGL((db_kernel<bf16_t, 8>), dim3((unsigned)g.K), dim3(1024), 0, st, g.N, g.K, (int)pq, (uint32_t)cpp, 1.0 / (double)cpp,
+                           (const bf16_t *)dY, db);
+    *err = hipGetLastError();
+    return true;
 }
 
 } // namespace cac

@@ -70,6 +70,7 @@ bool launch_producer_fast(const Geom &g, int dtype, const void *Y, const float *
                           hipStream_t st, hipError_t *err);
 hipError_t launch_producer_generic(const Geom &g, int dtype, const void *Y, const float *scale, const float *shift, void *Xn, void *Zn,
                                    void *Zin, hipStream_t st);
+bool launch_db_fast(const Geom &g, int dtype, const void *dY, float *db, hipStream_t st, hipError_t *err);
 size_t bn_bwd_workspace_bytes(const Geom &g, int dtype);
 bool launch_bn_bwd_fast(const Geom &g, int dtype, const void *Zin, const void *dY, const float *mean, const float *invstd,
                         const float *gamma, float *dgamma, float *dbeta, void *dX, void *ws, hipStream_t st, hipError_t *err);
