@@ -47,11 +47,22 @@ __global__ void __launch_bounds__(256) cosine_partial_kernel(const float *__rest
 
 __global__ void __launch_bounds__(64) cosine_final_kernel(const double *__restrict__ part, int nblocks, float *__restrict__ out)
 {
+    // every lane adds the partial sums k = lane, lane + 64, ... in that order, then lanes 0..2 add the
+    // 64 lane sums of one quantity each, lane by lane: a fixed order, and a chain of loads 64 times shorter
+    // than one thread walking all partial sums
+    __shared__ double lane_sum[3][64];
     __shared__ double tot[3];
+    double s[3] = {0.0, 0.0, 0.0};
+    for (int k = threadIdx.x; k < nblocks; k += 64)
+#pragma unroll
+        for (int q = 0; q < 3; ++q) s[q] += part[k * 3 + q];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) lane_sum[q][threadIdx.x] = s[q];
+    __syncthreads();
     if (threadIdx.x < 3) {
-        double s = 0.0;
-        for (int k = 0; k < nblocks; ++k) s += part[k * 3 + threadIdx.x];
-        tot[threadIdx.x] = s;
+        double t = 0.0;
+        for (int l = 0; l < 64; ++l) t += lane_sum[threadIdx.x][l];
+        tot[threadIdx.x] = t;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
