@@ -142,6 +142,101 @@ __global__ void __launch_bounds__(kT) bn_dx_kernel(Geom g, BnPlan q, const T *__
     }
 }
 
+// ---- rows of 10, 12 or 14 elements (bfloat16, 2 x 2 tiles, an even number of rows): the row-pair
+// records of compress.hip's narrow kernel.  Record r = (plane, pooled row) is 4*W contiguous bytes of
+// dY and dX and W contiguous bytes of Zin.
+template <int W> struct Narrow {
+    static constexpr int WP = W / 2, XB = 4 * W, NL = (XB + 15) / 16;
+    // the record's dY dwords (row 0: [0, WP), row 1: [WP, 2*WP)) and xh[j] = (Z[j] - mean) * invstd
+    static __device__ __forceinline__ void load(rsrc_t rs_dy, rsrc_t rs_z, uint32_t rec, bool live, float mu, float is, uint32_t (&d)[4 * NL],
+                                                float (&xh)[8])
+    {
+#pragma unroll
+        for (int k = 0; k < NL; ++k) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, live ? rec * (uint32_t)XB + 16u * k : kNoLoad, 0, 0);
+            d[4 * k] = v[0]; d[4 * k + 1] = v[1]; d[4 * k + 2] = v[2]; d[4 * k + 3] = v[3];
+        }
+        float z[8];
+        Chunk<bf16_t, 8>::load(rs_z, rec * (uint32_t)WP, live, true, z); // (a pooled row can start on an odd element)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xh[j] = (z[j] - mu) * is;
+    }
+};
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int W>
+__global__ void __launch_bounds__(kT) bn_partial_narrow_kernel(Geom g, BnPlan q, const bf16_t *__restrict__ Zin, const bf16_t *__restrict__ dY,
+                                                               const float *__restrict__ mean, const float *__restrict__ invstd,
+                                                               float *__restrict__ o_dy, float *__restrict__ o_dx)
+{
+    typedef Narrow<W> R;
+    __shared__ float red[2][kT / 64];
+    const int c = blockIdx.x / q.S, s = blockIdx.x - c * q.S;
+    const float mu = mean[c], is = invstd[c];
+    const rsrc_t rs = make_rsrc(dY, q.total * (uint32_t)R::XB), rs_z = make_rsrc(Zin, q.total * (uint32_t)(2 * R::WP));
+    const uint32_t end = min((uint32_t)(s + 1) * q.per_slice, q.per_channel);
+    float sdy = 0.f, sdx = 0.f;
+    for (uint32_t it = (uint32_t)s * q.per_slice + threadIdx.x; it < end; it += kT) {
+        const uint32_t n = udiv(it, q.inv_hp), i = it - n * g.Hp; // the channel's records: image by image
+        uint32_t d[4 * R::NL];
+        float xh[8];
+        R::load(rs, rs_z, (n * g.C + c) * g.Hp + i, true, mu, is, d, xh);
+#pragma unroll
+        for (int j = 0; j < R::WP; ++j) {
+            float t = 0.f;
+            t += bf_lo(d[j]); t += bf_hi(d[j]); t += bf_lo(d[R::WP + j]); t += bf_hi(d[R::WP + j]);
+            sdy += t;
+            sdx += t * xh[j];
+        }
+    }
+    sdy = wave_sum(sdy);
+    sdx = wave_sum(sdx);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) {
+        red[0][wave] = sdy;
+        red[1][wave] = sdx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        o_dy[blockIdx.x] = ((red[0][0] + red[0][1]) + red[0][2]) + red[0][3];
+        o_dx[blockIdx.x] = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];
+    }
+}
+
+template <int W>
+__global__ void __launch_bounds__(kT) bn_dx_narrow_kernel(Geom g, BnPlan q, const bf16_t *__restrict__ Zin, const bf16_t *__restrict__ dY,
+                                                          const float *__restrict__ mean, const float *__restrict__ invstd,
+                                                          const float *__restrict__ gamma, const float *__restrict__ dgamma,
+                                                          const float *__restrict__ dbeta, bf16_t *__restrict__ dX)
+{
+    typedef Narrow<W> R;
+    __shared__ __align__(16) unsigned char lds[4 * 64 * R::XB];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned char *buf = lds + wave * 64 * R::XB;
+    const uint32_t rec = blockIdx.x * (uint32_t)kT + threadIdx.x, first = rec - lane;
+    const bool live = rec < q.total, whole = first + 64 <= q.total;
+    const uint32_t plane = udiv(min(rec, q.total - 1), q.inv_hp);
+    const uint32_t c = plane - udiv(plane, q.inv_c) * (uint32_t)g.C;
+    const float inv_m = 1.0f / ((float)g.N * (float)(g.H * g.W));
+    const float mu = mean[c], is = invstd[c], k = gamma[c] * is;
+    const float mdy = dbeta[c] * inv_m, mdx = dgamma[c] * inv_m;
+    const rsrc_t rs = make_rsrc(dY, q.total * (uint32_t)R::XB), rs_z = make_rsrc(Zin, q.total * (uint32_t)(2 * R::WP));
+    uint32_t d[4 * R::NL];
+    float xh[8];
+    R::load(rs, rs_z, rec, live, mu, is, d, xh);
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    uint32_t o[W];
+#pragma unroll
+    for (int t = 0; t < W; ++t) {
+        const float x = xh[t < R::WP ? t : t - R::WP] * mdx;
+        o[t] = f32x2_to_bf16x2(k * (bf_lo(d[t]) - mdy - x), k * (bf_hi(d[t]) - mdy - x));
+    }
+#pragma unroll
+    for (int t = 0; t < W / 2; ++t) *(u32x2 *)(buf + lane * R::XB + 8 * t) = u32x2{o[2 * t], o[2 * t + 1]};
+    flush_records<R::XB>(buf, (unsigned char *)dX, first, lane, whole, live);
+}
+
 // db[o] = sum over n, p, q of dY[n,o,p,q] (bias-gradient formula of the compression figure): a block of
 // 1024 threads per output channel streams the channel's N planes (each a contiguous run) in 16-byte
 // chunks, two in flight per thread; fixed order, no scratch.
@@ -238,6 +333,40 @@ int plan_of(const Geom &g, int dtype, BnPlan *q)
     return ok ? epc : 0;
 }
 
+// Rows of 10, 12 or 14 bfloat16 under 2 x 2 tiles with an even number of rows: the record kernels.
+bool narrow_plan(const Geom &g, int dtype, BnPlan *q)
+{
+    if (dtype != CAC_BF16 || g.kh != 2 || g.kw != 2 || g.H % 2 || !(g.W == 10 || g.W == 12 || g.W == 14)) return false;
+    const long per_channel = (long)g.N * g.Hp, total = per_channel * g.C;
+    if (total * 4 * g.W >= (1L << 31) || g.Hp >= (1 << 16) || g.C >= (1 << 16)) return false; // 32-bit offsets, udiv's range
+    q->cpr = 1;
+    q->ipp = (uint32_t)g.Hp;
+    q->per_channel = (uint32_t)per_channel;
+    q->total = (uint32_t)total;
+    int S = (int)std::max(1L, std::min(64L, 2048L / g.C));
+    S = (int)std::max(1L, std::min((long)S, (per_channel + kT - 1) / kT));
+    q->per_slice = (uint32_t)((per_channel + S - 1) / S);
+    q->S = (int)((per_channel + q->per_slice - 1) / q->per_slice);
+    q->inv_cpr = 1.0;
+    q->inv_ipp = 1.0 / g.Hp;
+    q->inv_hp = 1.0 / g.Hp;
+    q->inv_c = 1.0 / g.C;
+    return true;
+}
+
+template <int W>
+void launch_narrow(const Geom &g, const BnPlan &q, const void *Zin, const void *dY, const float *mean, const float *invstd, const float *gamma,
+                   float *dgamma, float *dbeta, void *dX, float *ws, hipStream_t st)
+{
+    const bool one = q.S == 1;
+    float *o_dy = one ? dbeta : ws, *o_dx = one ? dgamma : ws + (size_t)g.C * q.S;
+    hipLaunchKernelGGL((bn_partial_narrow_kernel<W>), dim3((unsigned)(g.C * q.S)), dim3(kT), 0, st, g, q, (const bf16_t *)Zin, (const bf16_t *)dY,
+                       mean, invstd, o_dy, o_dx);
+    if (!one) hipLaunchKernelGGL(bn_finish_kernel, dim3((unsigned)g.C), dim3(64), 0, st, q.S, o_dy, o_dx, dgamma, dbeta);
+    hipLaunchKernelGGL((bn_dx_narrow_kernel<W>), dim3(cdiv(q.total, kT)), dim3(kT), 0, st, g, q, (const bf16_t *)Zin, (const bf16_t *)dY, mean,
+                       invstd, gamma, dgamma, dbeta, (bf16_t *)dX);
+}
+
 } // namespace
 
 // Bytes of device scratch launch_bn_bwd_fast needs (the slices' partial sums); 0 when a channel is
@@ -245,8 +374,8 @@ int plan_of(const Geom &g, int dtype, BnPlan *q)
 size_t bn_bwd_workspace_bytes(const Geom &g, int dtype)
 {
     BnPlan q;
-    if (!plan_of(g, dtype, &q) || q.S == 1) return 0;
-    return (size_t)2 * g.C * q.S * sizeof(float);
+    if (!narrow_plan(g, dtype, &q) && !plan_of(g, dtype, &q)) return 0;
+    return q.S == 1 ? 0 : (size_t)2 * g.C * q.S * sizeof(float);
 }
 
 // True when the chunk kernels cover the geometry (and have been launched).
@@ -254,6 +383,13 @@ bool launch_bn_bwd_fast(const Geom &g, int dtype, const void *Zin, const void *d
                         const float *gamma, float *dgamma, float *dbeta, void *dX, void *ws, hipStream_t st, hipError_t *err)
 {
     BnPlan q;
+    if (narrow_plan(g, dtype, &q)) {
+        if (g.W == 10) launch_narrow<10>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);
+        else if (g.W == 12) launch_narrow<12>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);
+        else launch_narrow<14>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);
+        *err = hipGetLastError();
+        return true;
+    }
     const int epc = plan_of(g, dtype, &q);
     if (!epc) return false;
     bool ok;

@@ -97,5 +97,32 @@ template <typename T, int EPC> __device__ __forceinline__ void store_chunk(T *ba
     }
 }
 
+// A wave's 64 records of BYTES bytes each, written by its lanes to the wave-private LDS region
+// `buf` (lane l at l * BYTES), to memory at dst + idx * BYTES: the records of a wave are contiguous
+// and start on a multiple of 16 bytes (first = index of lane 0's record, a multiple of 64), so they
+// leave as whole 16-byte pieces; the last wave of a tensor, when it is not full (`whole` false),
+// stores its live lanes' records two bytes at a time.
+template <int BYTES>
+__device__ __forceinline__ void flush_records(const unsigned char *buf, unsigned char *dst, uint32_t first, int lane, bool whole, bool live)
+{
+    static_assert(BYTES % 2 == 0, "");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (whole) {
+        unsigned char *base = dst + (size_t)first * BYTES;
+#pragma unroll
+        for (int k = 0; k < (4 * BYTES + 63) / 64; ++k) {
+            const int piece = lane + 64 * k;
+            if (piece < 4 * BYTES) *(u32x4 *)(base + 16 * piece) = *(const u32x4 *)(buf + 16 * piece);
+        }
+    } else if (live) {
+        const uint16_t *src = (const uint16_t *)(buf + lane * BYTES);
+        uint16_t *o = (uint16_t *)(dst + (size_t)(first + lane) * BYTES);
+#pragma unroll
+        for (int k = 0; k < BYTES / 2; ++k) o[k] = src[k];
+    }
+}
+
 } // namespace
 } // namespace cac

@@ -11,7 +11,6 @@
 // Ragged edges follow the ceil/valid rule: a tile that sticks out is averaged
 // over the elements it really has.
 #include "chunk.h"
-#include <type_traits>
 
 namespace cac {
 
@@ -206,27 +205,6 @@ __global__ void __launch_bounds__(256) compress_narrow_kernel(Geom g, const bf16
             out[j] = f32_to_bf16(g.pmax ? fmaxf(fmaxf(fmaxf(a, b), c), e) : sum * 0.25f);
         }
     };
-    // a wave's records (BYTES each) from LDS to memory as 16-byte pieces, or one by one for the
-    // last wave of the tensor when it is not full
-    auto flush = [&](unsigned char *buf, unsigned char *dst, auto bytes_c) {
-        constexpr int BYTES = decltype(bytes_c)::value;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (whole) {
-            unsigned char *base = dst + (size_t)first * BYTES;
-#pragma unroll
-            for (int k = 0; k < (4 * BYTES + 63) / 64; ++k) {
-                const int piece = lane + 64 * k;
-                if (piece < 4 * BYTES) *(u32x4 *)(base + 16 * piece) = *(const u32x4 *)(buf + 16 * piece);
-            }
-        } else if (live) {
-            const uint16_t *src = (const uint16_t *)(buf + lane * BYTES);
-            uint16_t *o = (uint16_t *)(dst + (size_t)idx * BYTES);
-#pragma unroll
-            for (int k = 0; k < BYTES / 2; ++k) o[k] = src[k];
-        }
-    };
     bf16_t zr[WP];
     if constexpr (PROD) {
         unsigned char *xbuf = zbuf + 64 * 2 * ZB;
@@ -235,7 +213,7 @@ __global__ void __launch_bounds__(256) compress_narrow_kernel(Geom g, const bf16
             pool(d, zr);
 #pragma unroll
             for (int j = 0; j < WP; ++j) ((bf16_t *)(zbuf + 64 * ZB))[lane * WP + j] = zr[j];
-            flush(zbuf + 64 * ZB, (unsigned char *)pr.Zin, std::integral_constant<int, ZB>{});
+            flush_records<ZB>(zbuf + 64 * ZB, (unsigned char *)pr.Zin, first, lane, whole, live);
         }
         // the next layer's input, rounded to its storage type; its pooled map from the rounded values
         const uint32_t plane = udiv(min(idx, total - 1), inv_hp);
@@ -247,12 +225,12 @@ __global__ void __launch_bounds__(256) compress_narrow_kernel(Geom g, const bf16
         typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 #pragma unroll
         for (int k = 0; k < W / 2; ++k) *(u32x2 *)(xbuf + lane * XB + 8 * k) = u32x2{d[2 * k], d[2 * k + 1]};
-        flush(xbuf, (unsigned char *)pr.Xn, std::integral_constant<int, XB>{});
+        flush_records<XB>(xbuf, (unsigned char *)pr.Xn, first, lane, whole, live);
     }
     pool(d, zr);
 #pragma unroll
     for (int j = 0; j < WP; ++j) ((bf16_t *)zbuf)[lane * WP + j] = zr[j];
-    flush(zbuf, (unsigned char *)Z, std::integral_constant<int, ZB>{});
+    flush_records<ZB>(zbuf, (unsigned char *)Z, first, lane, whole, live);
 }
 
 template <typename T, int EPC> bool launch_epc(const Geom &g, const void *X, void *Z, hipStream_t st, const Producer *prod = nullptr)
