@@ -146,20 +146,23 @@ __global__ void __launch_bounds__(kT) bn_dx_kernel(Geom g, BnPlan q, const T *__
 // records of compress.hip's narrow kernel.  Record r = (plane, pooled row) is 4*W contiguous bytes of
 // dY and dX and W contiguous bytes of Zin.
 template <int W> struct Narrow {
-    static constexpr int WP = W / 2, XB = 4 * W, NL = (XB + 15) / 16;
+    static constexpr int WP = W / 2, XB = 4 * W, NL = (XB + 15) / 16, NZ = (WP + 7) / 8;
     // the record's dY dwords (row 0: [0, WP), row 1: [WP, 2*WP)) and xh[j] = (Z[j] - mean) * invstd
     static __device__ __forceinline__ void load(rsrc_t rs_dy, rsrc_t rs_z, uint32_t rec, bool live, float mu, float is, uint32_t (&d)[4 * NL],
-                                                float (&xh)[8])
+                                                float (&xh)[8 * NZ])
     {
 #pragma unroll
         for (int k = 0; k < NL; ++k) {
             const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, live ? rec * (uint32_t)XB + 16u * k : kNoLoad, 0, 0);
             d[4 * k] = v[0]; d[4 * k + 1] = v[1]; d[4 * k + 2] = v[2]; d[4 * k + 3] = v[3];
         }
-        float z[8];
-        Chunk<bf16_t, 8>::load(rs_z, rec * (uint32_t)WP, live, true, z); // (a pooled row can start on an odd element)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) xh[j] = (z[j] - mu) * is;
+        for (int k = 0; k < NZ; ++k) {
+            float z[8];
+            Chunk<bf16_t, 8>::load(rs_z, rec * (uint32_t)WP + 8u * k, live, true, z); // (a pooled row can start on an odd element)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) xh[8 * k + j] = (z[j] - mu) * is;
+        }
     }
 };
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -180,7 +183,7 @@ __global__ void __launch_bounds__(kT) bn_partial_narrow_kernel(Geom g, BnPlan q,
     for (uint32_t it = (uint32_t)s * q.per_slice + threadIdx.x; it < end; it += kT) {
         const uint32_t n = udiv(it, q.inv_hp), i = it - n * g.Hp; // the channel's records: image by image
         uint32_t d[4 * R::NL];
-        float xh[8];
+        float xh[8 * R::NZ];
         R::load(rs, rs_z, (n * g.C + c) * g.Hp + i, true, mu, is, d, xh);
 #pragma unroll
         for (int j = 0; j < R::WP; ++j) {
@@ -223,7 +226,7 @@ __global__ void __launch_bounds__(kT) bn_dx_narrow_kernel(Geom g, BnPlan q, cons
     const float mdy = dbeta[c] * inv_m, mdx = dgamma[c] * inv_m;
     const rsrc_t rs = make_rsrc(dY, q.total * (uint32_t)R::XB), rs_z = make_rsrc(Zin, q.total * (uint32_t)(2 * R::WP));
     uint32_t d[4 * R::NL];
-    float xh[8];
+    float xh[8 * R::NZ];
     R::load(rs, rs_z, rec, live, mu, is, d, xh);
     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
     uint32_t o[W];
@@ -392,6 +395,21 @@ bool launch_bn_bwd_fast(const Geom &g, int dtype, const void *Zin, const void *d
     }
     const int epc = plan_of(g, dtype, &q);
     if (!epc) return false;
+    if (dtype == CAC_BF16 && g.kh == 2 && g.kw == 2 && g.H % 2 == 0 && g.W == 28 && (long)g.N * g.C * g.Hp * 4 * g.W < (1L << 31)) {
+        // rows of 28: the sums with the chunk kernel (the records' strided cold loads lose there, as
+        // in plain compression), the element-wise pass with the row-pair records (its stores gain)
+        const bool one = q.S == 1;
+        float *o_dy = one ? dbeta : (float *)ws, *o_dx = one ? dgamma : (float *)ws + (size_t)g.C * q.S;
+        hipLaunchKernelGGL((bn_partial_kernel<bf16_t, 8, 2, 2>), dim3((unsigned)(g.C * q.S)), dim3(kT), 0, st, g, q, (const bf16_t *)Zin,
+                           (const bf16_t *)dY, mean, invstd, o_dy, o_dx);
+        if (!one) hipLaunchKernelGGL(bn_finish_kernel, dim3((unsigned)g.C), dim3(64), 0, st, q.S, o_dy, o_dx, dgamma, dbeta);
+        BnPlan r = q;
+        r.total = (uint32_t)((long)g.N * g.C * g.Hp);
+        hipLaunchKernelGGL((bn_dx_narrow_kernel<28>), dim3(cdiv(r.total, kT)), dim3(kT), 0, st, g, r, (const bf16_t *)Zin, (const bf16_t *)dY,
+                           mean, invstd, gamma, dgamma, dbeta, (bf16_t *)dX);
+        *err = hipGetLastError();
+        return true;
+    }
     bool ok;
     if (dtype == CAC_F32)
         ok = launch_t<float, 4>(g, q, Zin, dY, mean, invstd, gamma, dgamma, dbeta, dX, (float *)ws, st);

@@ -80,7 +80,8 @@ def test_normalise_activate_compress(c):
 
 BN_CASES = CASES[:12] + [(16, 64, 28, 28, 2, 2, synth.BF16), (64, 64, 56, 56, 2, 2, synth.BF16), (256, 512, 14, 14, 2, 2, synth.BF16),
                          (5, 3, 4, 12, 2, 2, synth.BF16), (16, 64, 14, 14, 2, 2, synth.BF16), (3, 50, 14, 14, 2, 2, synth.BF16),
-                         (2, 7, 6, 10, 2, 2, synth.BF16), (2, 2100, 14, 14, 2, 2, synth.BF16)]
+                         (2, 7, 6, 10, 2, 2, synth.BF16), (2, 2100, 14, 14, 2, 2, synth.BF16), (9, 33, 28, 28, 2, 2, synth.BF16),
+                         (64, 512, 28, 28, 2, 2, synth.BF16)]
 
 
 @pytest.mark.parametrize("c", BN_CASES, ids=[" ".join(map(str, c)) for c in BN_CASES])
