@@ -350,6 +350,12 @@ def measure_peaks(B, torch, stream):
                       ("zeros", torch.zeros(16384, dtype=torch.bfloat16, device=dev))):
         ms = timed(torch, stream, lambda: B.cac_probe(B.PROBE_MFMA, src, sink, src.numel() * 2, iters, stream), 200, 20)
         out[f"mfma_bf16_tflops_{name}"] = round(flops / (ms * 1e-3) / 1e12, 1)
+    # the same flops with 16x16x32 MFMAs, and with one wave per SIMD instead of two (random numbers)
+    src = torch.randn(16384, dtype=torch.float32, device=dev).to(torch.bfloat16)
+    ms = timed(torch, stream, lambda: B.cac_probe(B.PROBE_MFMA_16X16, src, sink, src.numel() * 2, iters, stream), 200, 20)
+    out["mfma_bf16_tflops_random_16x16x32"] = round(flops / (ms * 1e-3) / 1e12, 1)
+    ms = timed(torch, stream, lambda: B.cac_probe(B.PROBE_MFMA_1WAVE, src, sink, src.numel() * 2, iters, stream), 200, 20)
+    out["mfma_bf16_tflops_random_one_wave_per_simd"] = round(flops / 2 / (ms * 1e-3) / 1e12, 1)
     n = 512 << 20
     a = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
     b = torch.empty(n, dtype=torch.uint8, device=dev)

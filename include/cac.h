@@ -48,7 +48,7 @@
 extern "C" {
 #endif
 
-#define CAC_VERSION 302 /* major*10000 + minor*100 + patch */
+#define CAC_VERSION 303 /* major*10000 + minor*100 + patch */
 
 typedef enum cac_status {
     CAC_OK = 0,
@@ -248,8 +248,12 @@ int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, c
  *                   MFMAs on fragments read once from src (at least 16 KiB; its VALUES matter: the
  *                   chip clocks lower on random numbers than on zeros); 2*32*32*16 flops each.
  *   CAC_PROBE_COPY: dst = src over `bytes` (a multiple of 16).   CAC_PROBE_READ: reads src.
- * dst: at least 8 KiB for the first and last kind. */
-typedef enum cac_probe_kind { CAC_PROBE_MFMA = 0, CAC_PROBE_COPY = 1, CAC_PROBE_READ = 2 } cac_probe_kind;
+ *   CAC_PROBE_MFMA_16X16: as CAC_PROBE_MFMA with 16x16x32 MFMAs, iters * 32 of them per wave (the same
+ *                   flops).   CAC_PROBE_MFMA_1WAVE: as CAC_PROBE_MFMA with 1024 waves, one per SIMD.
+ * dst: at least 8 KiB for every kind but the copy. */
+typedef enum cac_probe_kind {
+    CAC_PROBE_MFMA = 0, CAC_PROBE_COPY = 1, CAC_PROBE_READ = 2, CAC_PROBE_MFMA_16X16 = 3, CAC_PROBE_MFMA_1WAVE = 4
+} cac_probe_kind;
 int cac_probe(int kind, const void *src, void *dst, size_t bytes, int iters, void *stream);
 
 /* Bias gradient (bias-gradient formula in the same figure): db[o] = sum_{n,p,q} dY.

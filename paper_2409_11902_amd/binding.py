@@ -31,7 +31,7 @@ EXPORTS = (
     "conv_fwd_and_compress", "cac_compress", "conv_bwd_weight_compressed", "conv_bwd_data", "conv_bwd_bias", "cac_grad_cosine",
     "conv_bwd_weight_and_data", "conv_bwd_weight_compressed_noalloc", "cac_bn_relu_fwd_compress", "cac_bn_bwd_compressed", "cac_probe",
 )
-PROBE_MFMA, PROBE_COPY, PROBE_READ = 0, 1, 2
+PROBE_MFMA, PROBE_COPY, PROBE_READ, PROBE_MFMA_16X16, PROBE_MFMA_1WAVE = 0, 1, 2, 3, 4
 NOALLOC_SCRATCH_BYTES = 40 << 20
 
 

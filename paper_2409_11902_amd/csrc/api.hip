@@ -459,7 +459,7 @@ int cac_bn_bwd_compressed(const cac_desc *d, const void *Z_in, const void *dY, c
 int cac_probe(int kind, const void *src, void *dst, size_t bytes, int iters, void *stream)
 {
     int rc;
-    if (kind < CAC_PROBE_MFMA || kind > CAC_PROBE_READ) return fail(CAC_ERR_INVALID_ARG, "unknown probe kind %d", kind);
+    if (kind < CAC_PROBE_MFMA || kind > CAC_PROBE_MFMA_1WAVE) return fail(CAC_ERR_INVALID_ARG, "unknown probe kind %d", kind);
     if ((rc = check_ptr(src, "src")) || (rc = check_ptr(dst, "dst"))) return rc;
     if (bytes < 16384 || (bytes & 15)) return fail(CAC_ERR_INVALID_ARG, "bytes must be a multiple of 16, at least 16384");
     if (iters < 0 || iters > (1 << 24)) return fail(CAC_ERR_INVALID_ARG, "iters out of range");

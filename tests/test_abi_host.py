@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert B.cac_version() == 302
+    assert B.cac_version() == 303
 
 
 def test_desc_layout_matches_header():
@@ -250,7 +250,7 @@ def test_probe_validates_before_launching():
     L = B.lib()
     buf = ctypes.create_string_buffer(96)          # never dereferenced: every call below is refused
     p = ctypes.c_void_p((ctypes.addressof(buf) + 15) & ~15)
-    assert L.cac_probe(3, p, p, ctypes.c_size_t(1 << 20), 1, None) == B.ERR_INVALID_ARG
+    assert L.cac_probe(5, p, p, ctypes.c_size_t(1 << 20), 1, None) == B.ERR_INVALID_ARG
     assert L.cac_probe(-1, p, p, ctypes.c_size_t(1 << 20), 1, None) == B.ERR_INVALID_ARG
     assert L.cac_probe(B.PROBE_COPY, None, p, ctypes.c_size_t(1 << 20), 0, None) == B.ERR_INVALID_ARG
     assert L.cac_probe(B.PROBE_COPY, p, None, ctypes.c_size_t(1 << 20), 0, None) == B.ERR_INVALID_ARG

@@ -350,4 +350,6 @@ def test_probe_kernels_run_and_the_copy_copies():
     out = torch.zeros(8192, dtype=torch.uint8, device="cuda:0")
     B.cac_probe(B.PROBE_READ, src, out, n)
     B.cac_probe(B.PROBE_MFMA, src, out, n, iters=4)
+    B.cac_probe(B.PROBE_MFMA_16X16, src, out, n, iters=4)
+    B.cac_probe(B.PROBE_MFMA_1WAVE, src, out, n, iters=4)
     torch.cuda.synchronize()
